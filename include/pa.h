@@ -1,0 +1,174 @@
+/*
+ * pa.h - C ABI of libpa: paged single-query attention for AMD MI355X (gfx950).
+ *
+ * The library implements the decode-step hot path of PagedAttention
+ * (arxiv 2309.06180): attention of one query token per sequence over a KV
+ * cache kept in fixed-size physical blocks that each sequence reaches through
+ * a block table (Sec. 4.1, 4.2), the store of new K/V vectors into those
+ * blocks (Sec. 4.3, 5.1 (1)) and the batched copy-on-write block copy
+ * (Sec. 4.4, 5.1 (3)).
+ *
+ * Conventions shared by all calls
+ * -------------------------------
+ * Shapes: S sequences, H heads, D head dimension, B tokens per block, NB
+ * physical blocks in the pool, T new tokens, MB block-table row stride.
+ *
+ * Cache layout: a K (or V) cache of one layer is an array [NB][H][B][D] of
+ * `dtype` elements; element (block pb, head h, offset off, dim d) is at index
+ * ((pb*H + h)*B + off)*D + d.  K and V use the same layout.  Token t of a
+ * sequence lives in the sequence's logical block t / B at offset t % B; its
+ * slot number is physical_block*B + offset.
+ *
+ * Memory: every data pointer is DEVICE memory owned by the caller, 16-byte
+ * aligned, unless a parameter says "host".  The library allocates and frees
+ * nothing the caller can see, never synchronises, and enqueues all work on
+ * `stream` (a hipStream_t passed as void*; NULL is the default stream).
+ *
+ * Errors: host-checkable conditions are reported synchronously through
+ * pa_status and nothing is launched.  Contents of index arrays live on the
+ * device and are NOT checked by the compute calls: a block id outside
+ * [0, NB), a context length above max_context_len or above MB*B, a slot at or
+ * above NB*B, duplicate slots, or a copy destination that is also a source or
+ * appears twice are undefined behaviour.  pa_debug_validate checks them.
+ *
+ * Supported: dtype f16/bf16/f32; D*sizeof(elem) in {128, 256, 512} bytes
+ * (D = 64, 128, 256 at 2 bytes; D = 32, 64, 128 at 4 bytes); B in
+ * {8, 16, 32, 64, 128} with B*D*sizeof(elem) >= 1024; multi-head attention
+ * with as many KV heads as query heads (the paper's models).
+ */
+#ifndef PA_H
+#define PA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PA_OK = 0,
+    PA_ERR_NULL = 1,        /* a required pointer is NULL                         */
+    PA_ERR_SHAPE = 2,       /* a size is negative, zero where it may not be, or inconsistent */
+    PA_ERR_UNSUPPORTED = 3, /* (dtype, head_dim, block_size) outside the supported set */
+    PA_ERR_ALIGN = 4,       /* a data pointer is not 16-byte aligned              */
+    PA_ERR_WORKSPACE = 5,   /* workspace missing or too small                     */
+    PA_ERR_HIP = 6,         /* the HIP runtime refused a launch or a copy         */
+    PA_ERR_INVALID = 7      /* pa_debug_validate found a bad index                */
+} pa_status;
+
+typedef enum { PA_F32 = 0, PA_F16 = 1, PA_BF16 = 2 } pa_dtype;
+
+/* partition_size value that lets the library choose the split (needs a workspace). */
+#define PA_PARTITION_AUTO (-1)
+
+/*
+ * pa_decode - single-query attention over the paged cache.
+ *
+ * For every sequence s and head h, with n = context_lens[s]:
+ *     x_t   = scale * sum_d q[s][h][d] * K[t][h][d]              t = 0..n-1
+ *     out[s][h][:] = sum_t softmax(x)_t * V[t][h][:]
+ * where K[t], V[t] are read from physical block block_tables[s][t / B] at
+ * offset t % B.  This is Eq. (4) of Sec. 4.1, equal to the per-token attention
+ * of Sec. 2.1; the query token is token n-1, so its K/V must already be in
+ * the cache (call pa_reshape_and_cache first, Sec. 4.3).  Arithmetic is fp32;
+ * the result is rounded to `dtype` once (nearest even).  n = 0 gives a zero
+ * row.  Table entries at or beyond ceil(n / B) and cache slots at or beyond n
+ * are never used (they may hold anything, NaN included).
+ *
+ *   out              [S][H][D] dtype, written
+ *   q                [S][H][D] dtype
+ *   k_cache, v_cache [NB][H][B][D] dtype
+ *   block_tables     [S][max_blocks_per_seq] int32
+ *   context_lens     [S] int32, each <= max_context_len <= max_blocks_per_seq*B
+ *   max_context_len  host-known upper bound on context_lens[]
+ *   partition_size   0: one pass per (sequence, head).
+ *                    > 0, multiple of B: split-context - every (sequence, head)
+ *                    is cut into ranges of partition_size tokens processed
+ *                    independently (max logit, exp-sum and normalised partial
+ *                    output kept in fp32 in the workspace), then a second
+ *                    kernel merges them with the log-sum-exp rule.
+ *                    PA_PARTITION_AUTO: the library picks a partition size
+ *                    from the shape; falls back to one pass when workspace is
+ *                    NULL.
+ *   workspace        device scratch of at least pa_decode_workspace_bytes(...)
+ *                    bytes when a split is used; contents undefined after.
+ *
+ * Returns PA_OK without launching when S == 0.
+ */
+pa_status pa_decode(void *out, const void *q, const void *k_cache, const void *v_cache,
+                    const int32_t *block_tables, int32_t max_blocks_per_seq,
+                    const int32_t *context_lens, int32_t num_seqs, int32_t num_heads,
+                    int32_t head_dim, int32_t block_size, int64_t num_blocks, pa_dtype dtype,
+                    float scale, int32_t max_context_len, int32_t partition_size,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of workspace pa_decode needs for this shape and partition_size (0 for one pass). */
+size_t pa_decode_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t head_dim,
+                                 int32_t block_size, int32_t max_context_len,
+                                 int32_t partition_size);
+
+/*
+ * pa_reshape_and_cache - store new K/V vectors into the paged cache
+ * (Sec. 4.3: the KV of the tokens of this iteration is saved into the
+ * physical blocks; Sec. 5.1 (1): reshape and block write fused in one launch).
+ *
+ * For every token t with slot = slot_mapping[t] >= 0 and every head h:
+ *     k_cache[slot / B][h][slot % B][:] = k[t][h][:]     (same for v)
+ * Bit patterns are copied unchanged.  Negative slots are skipped.
+ *
+ *   k, v          [T][H][D] dtype
+ *   slot_mapping  [T] int64
+ * Returns PA_OK without launching when T == 0.
+ */
+pa_status pa_reshape_and_cache(const void *k, const void *v, void *k_cache, void *v_cache,
+                               const int64_t *slot_mapping, int32_t num_tokens,
+                               int32_t num_heads, int32_t head_dim, int32_t block_size,
+                               int64_t num_blocks, pa_dtype dtype, void *stream);
+
+/*
+ * pa_copy_blocks - copy-on-write block copies, all pairs and all layers in
+ * one launch (Sec. 4.4: a shared block that is about to be written is copied
+ * to a fresh block; Sec. 5.1 (3): the copies are batched into one kernel).
+ *
+ * For every layer l and pair i: k_caches[l][dst_i] = k_caches[l][src_i] and the
+ * same for v - the whole block, all heads, all B slots.
+ *
+ *   k_caches, v_caches  HOST arrays of num_layers device pointers, each a
+ *                       [NB][H][B][D] cache; read during the call only
+ *   src_dst_pairs       device [num_pairs][2] int64, (src, dst) block ids
+ * Returns PA_OK without launching when num_pairs == 0.
+ */
+pa_status pa_copy_blocks(void *const *k_caches, void *const *v_caches, int32_t num_layers,
+                         const int64_t *src_dst_pairs, int32_t num_pairs, int32_t num_heads,
+                         int32_t head_dim, int32_t block_size, int64_t num_blocks,
+                         pa_dtype dtype, void *stream);
+
+/*
+ * pa_debug_validate - check the device index arrays of a decode step against
+ * the undefined-behaviour list above.  Copies them to the host, synchronises
+ * the stream, and returns PA_ERR_INVALID on the first violation.  Any of
+ * block_tables/context_lens, slot_mapping, src_dst_pairs may be NULL to skip
+ * that check.  For tests and bring-up, not for the serving loop.
+ */
+pa_status pa_debug_validate(const int32_t *block_tables, int32_t max_blocks_per_seq,
+                            const int32_t *context_lens, int32_t num_seqs,
+                            int32_t max_context_len, const int64_t *slot_mapping,
+                            int32_t num_tokens, const int64_t *src_dst_pairs, int32_t num_pairs,
+                            int32_t block_size, int64_t num_blocks, void *stream);
+
+/*
+ * pa_stream_read - bandwidth probe: sums `bytes` bytes (multiple of 16) at
+ * `src` with 16-byte loads and writes one 4-byte word per workgroup to `sink`
+ * (at least 4*65536 bytes).  Gives the streaming-read ceiling of the device
+ * that roofline fractions are compared with.
+ */
+pa_status pa_stream_read(const void *src, size_t bytes, void *sink, void *stream);
+
+const char *pa_status_string(pa_status status);
+int pa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PA_H */

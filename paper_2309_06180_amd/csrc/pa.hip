@@ -1,0 +1,834 @@
+// libpa - paged single-query attention for gfx950 (MI355X).
+//
+// Three operations of PagedAttention's decode step (arxiv 2309.06180):
+//   pa_decode            Sec. 4.1, Eq. (4): attention of one query per sequence
+//                        over K/V blocks reached through a block table
+//   pa_reshape_and_cache Sec. 4.3 / 5.1 (1): store new K/V vectors at their slots
+//   pa_copy_blocks       Sec. 4.4 / 5.1 (3): batched copy-on-write block copies
+//
+// Cache layout [NB][H][B][D]: the K (or V) vectors of one (block, head) are
+// B*D*E contiguous bytes, a token row is D*E bytes.  Every wavefront load is
+// 64 lanes x 16 bytes = 1 KiB of consecutive addresses.
+//
+// The decode path is a batch of matrix-vector products (one flop per byte of
+// KV at 2-byte elements), bound by HBM bandwidth, so there is no MFMA here:
+// the design goal is bytes in flight per compute unit and few VALU
+// instructions per byte.
+#include <hip/hip_runtime.h>
+
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <type_traits>
+
+#include "pa.h"
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+// running-maximum start value: finite, so that (m - m) is 0 and never NaN
+constexpr float kNegBig = -3.0e38f;
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// ---- cross-lane sums ------------------------------------------------------
+// DPP controls: quad_perm [1,0,3,2] = 0xB1, quad_perm [2,3,0,1] = 0x4E,
+// row_half_mirror = 0x141, row_mirror = 0x140.  Applied in this order they
+// form a butterfly over 4, 8 and 16 consecutive lanes; every lane ends with
+// the same bits because each step adds the same two partial sums.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x)
+{
+    int y = __builtin_amdgcn_update_dpp(0, (int)as_u32(x), CTRL, 0xf, 0xf, true);
+    return x + as_f32((uint32_t)y);
+}
+
+template <int LANES>
+__device__ __forceinline__ float group_sum(float x)
+{
+    static_assert(LANES == 8 || LANES == 16 || LANES == 32, "lanes per token row");
+    x = dpp_add<0xB1>(x);
+    x = dpp_add<0x4E>(x);
+    x = dpp_add<0x141>(x);
+    if (LANES >= 16) x = dpp_add<0x140>(x);
+    if (LANES >= 32) x += __shfl_xor(x, 16);
+    return x;
+}
+
+// ---- element types -------------------------------------------------------
+// A lane always holds one 16-byte fragment of a token row: 8 two-byte
+// elements or 4 floats.
+template <int DT> struct Traits;
+
+template <> struct Traits<PA_F32> {
+    static constexpr int E = 4, EPL = 4;
+    static __device__ __forceinline__ float dot(const uint4 &k, const uint4 &q, float acc)
+    {
+        acc = __builtin_fmaf(as_f32(k.x), as_f32(q.x), acc);
+        acc = __builtin_fmaf(as_f32(k.y), as_f32(q.y), acc);
+        acc = __builtin_fmaf(as_f32(k.z), as_f32(q.z), acc);
+        acc = __builtin_fmaf(as_f32(k.w), as_f32(q.w), acc);
+        return acc;
+    }
+    static __device__ __forceinline__ void axpy(float (&acc)[4], float p, const uint4 &v)
+    {
+        acc[0] = __builtin_fmaf(p, as_f32(v.x), acc[0]);
+        acc[1] = __builtin_fmaf(p, as_f32(v.y), acc[1]);
+        acc[2] = __builtin_fmaf(p, as_f32(v.z), acc[2]);
+        acc[3] = __builtin_fmaf(p, as_f32(v.w), acc[3]);
+    }
+    static __device__ __forceinline__ uint4 pack(const float (&x)[4])
+    {
+        return make_uint4(as_u32(x[0]), as_u32(x[1]), as_u32(x[2]), as_u32(x[3]));
+    }
+};
+
+template <> struct Traits<PA_F16> {
+    static constexpr int E = 2, EPL = 8;
+    static __device__ __forceinline__ float dot(const uint4 &k, const uint4 &q, float acc)
+    {
+        // products of two halves are exact in fp32; accumulation is fp32
+        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, k.x), __builtin_bit_cast(half2_t, q.x), acc, false);
+        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, k.y), __builtin_bit_cast(half2_t, q.y), acc, false);
+        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, k.z), __builtin_bit_cast(half2_t, q.z), acc, false);
+        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, k.w), __builtin_bit_cast(half2_t, q.w), acc, false);
+        return acc;
+    }
+    static __device__ __forceinline__ void axpy2(float &a0, float &a1, float p, uint32_t v)
+    {
+        half2_t h = __builtin_bit_cast(half2_t, v);
+        a0 = __builtin_fmaf(p, (float)h.x, a0);
+        a1 = __builtin_fmaf(p, (float)h.y, a1);
+    }
+    static __device__ __forceinline__ void axpy(float (&acc)[8], float p, const uint4 &v)
+    {
+        axpy2(acc[0], acc[1], p, v.x);
+        axpy2(acc[2], acc[3], p, v.y);
+        axpy2(acc[4], acc[5], p, v.z);
+        axpy2(acc[6], acc[7], p, v.w);
+    }
+    static __device__ __forceinline__ uint32_t pack2(float a, float b)
+    {
+        half2_t h;
+        h.x = (_Float16)a;   // round to nearest even
+        h.y = (_Float16)b;
+        return __builtin_bit_cast(uint32_t, h);
+    }
+    static __device__ __forceinline__ uint4 pack(const float (&x)[8])
+    {
+        return make_uint4(pack2(x[0], x[1]), pack2(x[2], x[3]), pack2(x[4], x[5]), pack2(x[6], x[7]));
+    }
+};
+
+template <> struct Traits<PA_BF16> {
+    static constexpr int E = 2, EPL = 8;
+    static __device__ __forceinline__ float dot(const uint4 &k, const uint4 &q, float acc)
+    {
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.x), __builtin_bit_cast(bf16x2_t, q.x), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.y), __builtin_bit_cast(bf16x2_t, q.y), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.z), __builtin_bit_cast(bf16x2_t, q.z), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.w), __builtin_bit_cast(bf16x2_t, q.w), acc, false);
+        return acc;
+    }
+    static __device__ __forceinline__ void axpy2(float &a0, float &a1, float p, uint32_t v)
+    {
+        // a bfloat16 is the upper half of a float
+        a0 = __builtin_fmaf(p, as_f32(v << 16), a0);
+        a1 = __builtin_fmaf(p, as_f32(v & 0xffff0000u), a1);
+    }
+    static __device__ __forceinline__ void axpy(float (&acc)[8], float p, const uint4 &v)
+    {
+        axpy2(acc[0], acc[1], p, v.x);
+        axpy2(acc[2], acc[3], p, v.y);
+        axpy2(acc[4], acc[5], p, v.z);
+        axpy2(acc[6], acc[7], p, v.w);
+    }
+    static __device__ __forceinline__ uint32_t rne(float f)
+    {
+        uint32_t u = as_u32(f);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // NaN stays NaN
+        return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    }
+    static __device__ __forceinline__ uint4 pack(const float (&x)[8])
+    {
+        return make_uint4(rne(x[0]) | (rne(x[1]) << 16), rne(x[2]) | (rne(x[3]) << 16),
+                          rne(x[4]) | (rne(x[5]) << 16), rne(x[6]) | (rne(x[7]) << 16));
+    }
+};
+
+__device__ __forceinline__ uint4 load16(const char *p)
+{
+    return *reinterpret_cast<const uint4 *>(p);
+}
+
+// ---- decode ----------------------------------------------------------------
+// One workgroup of W wavefronts serves one (sequence, head[, partition]).
+//
+// Lane roles: a token row is LPT = D*E/16 lanes wide, so one 1 KiB wavefront
+// load covers TPL = 64/LPT consecutive tokens; lane = g*LPT + c holds
+// dimensions [c*EPL, (c+1)*EPL) of token (base + g).  Work advances in chunks
+// of LPC loads (CT = LPC*TPL tokens, at most one block); wave w takes chunks
+// w, w+W, ...; U chunks (2*U*LPC KiB of K and V) are requested together
+// before any of them is used.
+//
+// Each group g of lanes runs its own online softmax over the tokens it sees
+// (running maximum m, sum l, weighted V sum acc, all fp32, exponents in base
+// 2 with log2(e) folded into the scale).  Groups and waves are merged once at
+// the end with the log-sum-exp rule, so the inner loop has no cross-group
+// traffic.  Summation order depends only on logical token positions, so the
+// result does not change with the physical placement of blocks.
+template <int DT, int D, int B, int W, int U, bool PART>
+__global__ __launch_bounds__(W *kWave) void pa_decode_kernel(
+    void *__restrict__ out, const void *__restrict__ q, const char *__restrict__ k_cache,
+    const char *__restrict__ v_cache, const int32_t *__restrict__ block_tables, int32_t max_blocks,
+    const int32_t *__restrict__ context_lens, int32_t H, float scale_log2, int32_t partition_size,
+    int32_t max_parts, float *__restrict__ ws_acc, float *__restrict__ ws_ml)
+{
+    using Tr = Traits<DT>;
+    constexpr int E = Tr::E, EPL = Tr::EPL;
+    constexpr int ROW_BYTES = D * E;
+    constexpr int LPT = ROW_BYTES / 16;
+    constexpr int TPL = kWave / LPT;
+    constexpr int LPC = (B / TPL) < 4 ? (B / TPL) : 4;
+    constexpr int CT = LPC * TPL;
+    constexpr int64_t TILE_BYTES = (int64_t)B * ROW_BYTES;
+    static_assert(LPT >= 8 && LPT <= 32 && B % TPL == 0 && B % CT == 0 && LPC >= 1, "shape");
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int g = lane / LPT;
+    const int c = lane % LPT;
+    const uint32_t lane16 = (uint32_t)lane * 16u;
+
+    int item = blockIdx.x;
+    const int h = item % H;
+    item /= H;
+    const int part = PART ? item % max_parts : 0;
+    const int s = PART ? item / max_parts : item;
+
+    const int n = context_lens[s];
+    const int t_begin = PART ? part * partition_size : 0;
+    const int t_end = PART ? (t_begin + partition_size < n ? t_begin + partition_size : n) : n;
+    if (t_begin >= t_end) {
+        if (!PART && w == 0 && g == 0) {
+            // empty context: zero row
+            reinterpret_cast<uint4 *>(out)[((int64_t)s * H + h) * LPT + c] = make_uint4(0, 0, 0, 0);
+        }
+        return;
+    }
+
+    const uint4 qf = reinterpret_cast<const uint4 *>(q)[((int64_t)s * H + h) * LPT + c];
+    const int32_t *__restrict__ table = block_tables + (int64_t)s * max_blocks;
+    const int nchunks = (t_end - t_begin + CT - 1) / CT;
+
+    float m = kNegBig, l = 0.f;
+    float acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+
+    struct Chunk {
+        uint4 k[LPC], v[LPC];
+    };
+
+    auto block_of = [&](int ci) -> int {
+        // ci is wave-uniform: this is a scalar load
+        return table[(t_begin + ci * CT) / B];
+    };
+    auto issue = [&](Chunk &ck, int ci, int pb) {
+        const int t0 = t_begin + ci * CT;
+        const int64_t off = ((int64_t)pb * H + h) * TILE_BYTES + (int64_t)(t0 % B) * ROW_BYTES;
+        const char *kp = k_cache + off + lane16;
+        const char *vp = v_cache + off + lane16;
+#pragma unroll
+        for (int i = 0; i < LPC; ++i) ck.k[i] = load16(kp + i * 1024);
+#pragma unroll
+        for (int i = 0; i < LPC; ++i) ck.v[i] = load16(vp + i * 1024);
+    };
+    // MASK is set only for a chunk that may reach past t_end (the last one)
+    auto consume = [&](Chunk &ck, int ci, auto mask_tag) {
+        constexpr bool MASK = decltype(mask_tag)::value;
+        const int t0 = t_begin + ci * CT;
+        float x[LPC];
+#pragma unroll
+        for (int i = 0; i < LPC; ++i) x[i] = group_sum<LPT>(Tr::dot(ck.k[i], qf, 0.f)) * scale_log2;
+        if (MASK) {
+            // slots at or past t_end hold no token and may contain anything, NaN
+            // included - select them away, never multiply
+#pragma unroll
+            for (int i = 0; i < LPC; ++i) {
+                const bool dead = t0 + i * TPL + g >= t_end;
+                x[i] = dead ? -INFINITY : x[i];
+                ck.v[i].x = dead ? 0u : ck.v[i].x;
+                ck.v[i].y = dead ? 0u : ck.v[i].y;
+                ck.v[i].z = dead ? 0u : ck.v[i].z;
+                ck.v[i].w = dead ? 0u : ck.v[i].w;
+            }
+        }
+        float m_new = m;
+#pragma unroll
+        for (int i = 0; i < LPC; ++i) m_new = fmaxf(m_new, x[i]);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        float p[LPC], psum = 0.f;
+#pragma unroll
+        for (int i = 0; i < LPC; ++i) {
+            p[i] = __builtin_amdgcn_exp2f(x[i] - m_new);
+            psum += p[i];
+        }
+        l = l * alpha + psum;
+        m = m_new;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] *= alpha;
+#pragma unroll
+        for (int i = 0; i < LPC; ++i) Tr::axpy(acc, p[i], ck.v[i]);
+    };
+    const std::false_type full{};
+    const std::true_type masked{};
+
+    // Steady state: U chunks per trip, all loads issued up front, then consumed
+    // in order, in one straight-line block (nothing loaded is carried across the
+    // back edge, so the compiler waits exactly for the fragment it needs next).
+    // Chunks before the last one of the range are full; the remainder loop takes
+    // one chunk at a time with masking.  Latency is hidden by the other waves
+    // resident on the SIMD.
+    {
+        int ci = w;
+        for (; ci + (U - 1) * W <= nchunks - 2; ci += U * W) {
+            Chunk ck[U];
+            int pb[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) pb[u] = block_of(ci + u * W);
+#pragma unroll
+            for (int u = 0; u < U; ++u) issue(ck[u], ci + u * W, pb[u]);
+#pragma unroll
+            for (int u = 0; u < U; ++u) consume(ck[u], ci + u * W, full);
+        }
+        for (; ci < nchunks; ci += W) {
+            Chunk ck;
+            issue(ck, ci, block_of(ci));
+            consume(ck, ci, masked);
+        }
+    }
+
+    // merge the TPL token groups of this wave (lanes with equal c)
+    {
+        float M = m;
+#pragma unroll
+        for (int d = LPT; d < kWave; d <<= 1) M = fmaxf(M, __shfl_xor(M, d));
+        const float f = __builtin_amdgcn_exp2f(m - M);
+        l *= f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] *= f;
+#pragma unroll
+        for (int d = LPT; d < kWave; d <<= 1) {
+            l += __shfl_xor(l, d);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], d);
+        }
+        m = M;
+    }
+
+    // merge the W waves of the workgroup through LDS
+    if (W > 1) {
+        __shared__ float sm_acc[W][D];
+        __shared__ float sm_m[W], sm_l[W];
+        if (g == 0) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) sm_acc[w][c * EPL + e] = acc[e];
+            if (c == 0) {
+                sm_m[w] = m;
+                sm_l[w] = l;
+            }
+        }
+        __syncthreads();
+        if (w != 0) return;
+        float M = sm_m[0];
+#pragma unroll
+        for (int i = 1; i < W; ++i) M = fmaxf(M, sm_m[i]);
+        l = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+#pragma unroll
+        for (int i = 0; i < W; ++i) {
+            const float f = __builtin_amdgcn_exp2f(sm_m[i] - M);
+            l = __builtin_fmaf(sm_l[i], f, l);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] = __builtin_fmaf(sm_acc[i][c * EPL + e], f, acc[e]);
+        }
+        m = M;
+    }
+    if (g != 0) return;
+
+    if (PART) {
+        // unnormalised partial: the reduce kernel divides once
+        const int64_t slot = ((int64_t)s * H + h) * max_parts + part;
+        float *dst = ws_acc + slot * D + c * EPL;
+#pragma unroll
+        for (int e = 0; e < EPL; e += 4)
+            *reinterpret_cast<float4 *>(dst + e) = make_float4(acc[e], acc[e + 1], acc[e + 2], acc[e + 3]);
+        if (c == 0) *reinterpret_cast<float2 *>(ws_ml + slot * 2) = make_float2(m, l);
+    } else {
+        const float inv = 1.0f / l;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] *= inv;
+        reinterpret_cast<uint4 *>(out)[((int64_t)s * H + h) * LPT + c] = Tr::pack(acc);
+    }
+}
+
+// Merge of the split-context partials: out = sum_p 2^(m_p-M) a_p / sum_p 2^(m_p-M) l_p
+// with a_p the unnormalised partial sums.  One wavefront per (sequence, head);
+// lane c handles the same 16-byte output fragment as in the decode kernel.
+template <int DT, int D>
+__global__ __launch_bounds__(kWave) void pa_reduce_kernel(
+    void *__restrict__ out, const int32_t *__restrict__ context_lens, int32_t H,
+    int32_t partition_size, int32_t max_parts, const float *__restrict__ ws_acc,
+    const float *__restrict__ ws_ml)
+{
+    using Tr = Traits<DT>;
+    constexpr int EPL = Tr::EPL;
+    constexpr int LPT = D * Tr::E / 16;
+    const int c = threadIdx.x;
+    if (c >= LPT) return;
+    const int h = blockIdx.x % H;
+    const int s = blockIdx.x / H;
+    const int n = context_lens[s];
+    int parts = (n + partition_size - 1) / partition_size;
+    if (parts > max_parts) parts = max_parts;
+    const int64_t base = ((int64_t)s * H + h) * max_parts;
+    float acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+    if (parts > 0) {
+        float M = kNegBig;
+        for (int p = 0; p < parts; ++p) M = fmaxf(M, ws_ml[(base + p) * 2]);
+        float l = 0.f;
+        for (int p = 0; p < parts; ++p) {
+            const float2 ml = *reinterpret_cast<const float2 *>(ws_ml + (base + p) * 2);
+            const float f = __builtin_amdgcn_exp2f(ml.x - M);
+            l = __builtin_fmaf(ml.y, f, l);
+            const float *src = ws_acc + (base + p) * D + c * EPL;
+#pragma unroll
+            for (int e = 0; e < EPL; e += 4) {
+                const float4 a = *reinterpret_cast<const float4 *>(src + e);
+                acc[e] = __builtin_fmaf(a.x, f, acc[e]);
+                acc[e + 1] = __builtin_fmaf(a.y, f, acc[e + 1]);
+                acc[e + 2] = __builtin_fmaf(a.z, f, acc[e + 2]);
+                acc[e + 3] = __builtin_fmaf(a.w, f, acc[e + 3]);
+            }
+        }
+        const float inv = 1.0f / l;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] *= inv;
+    }
+    reinterpret_cast<uint4 *>(out)[((int64_t)s * H + h) * LPT + c] = Tr::pack(acc);
+}
+
+// ---- reshape_and_cache -------------------------------------------------------
+// One thread moves one 16-byte fragment.  A token is frags_per_token = H*D*E/16
+// fragments; fragment r of token t belongs to head r / frags_per_row.
+__global__ __launch_bounds__(256) void reshape_and_cache_kernel(
+    const uint4 *__restrict__ k, const uint4 *__restrict__ v, uint4 *__restrict__ k_cache,
+    uint4 *__restrict__ v_cache, const int64_t *__restrict__ slot_mapping, int64_t total_frags,
+    int32_t frags_per_token, int32_t frags_per_row, int32_t block_size)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total_frags) return;
+    const int64_t t = idx / frags_per_token;
+    const int32_t r = (int32_t)(idx - t * frags_per_token);
+    const int64_t slot = slot_mapping[t];
+    if (slot < 0) return;
+    const int64_t pb = slot / block_size;
+    const int32_t off = (int32_t)(slot - pb * block_size);
+    const int32_t h = r / frags_per_row;
+    const int32_t cfrag = r - h * frags_per_row;
+    // [NB][H][B][D] in fragments: ((pb*H + h)*B + off)*frags_per_row + cfrag
+    const int32_t H = frags_per_token / frags_per_row;
+    const int64_t dst = ((pb * H + h) * block_size + off) * frags_per_row + cfrag;
+    const uint4 *src = blockIdx.y ? v : k;
+    uint4 *cache = blockIdx.y ? v_cache : k_cache;
+    cache[dst] = src[idx];
+}
+
+// ---- copy_blocks -------------------------------------------------------------
+constexpr int kMaxCopyPtrs = 128;   // K and V pointers of up to 64 layers per launch
+struct CachePtrs {
+    uint4 *p[kMaxCopyPtrs];
+};
+
+// grid = (slices of a block, pairs, caches); a block of one cache is
+// frags_per_block consecutive 16-byte fragments.
+__global__ __launch_bounds__(256) void copy_blocks_kernel(CachePtrs caches,
+                                                           const int64_t *__restrict__ pairs,
+                                                           int64_t frags_per_block)
+{
+    constexpr int UNROLL = 4;
+    uint4 *cache = caches.p[blockIdx.z];
+    const int64_t src = pairs[2 * (int64_t)blockIdx.y];
+    const int64_t dst = pairs[2 * (int64_t)blockIdx.y + 1];
+    const uint4 *sp = cache + src * frags_per_block;
+    uint4 *dp = cache + dst * frags_per_block;
+    const int64_t base = (int64_t)blockIdx.x * (256 * UNROLL) + threadIdx.x;
+    uint4 tmp[UNROLL];
+#pragma unroll
+    for (int i = 0; i < UNROLL; ++i) {
+        const int64_t f = base + i * 256;
+        if (f < frags_per_block) tmp[i] = sp[f];
+    }
+#pragma unroll
+    for (int i = 0; i < UNROLL; ++i) {
+        const int64_t f = base + i * 256;
+        if (f < frags_per_block) dp[f] = tmp[i];
+    }
+}
+
+// ---- bandwidth probe ---------------------------------------------------------
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restrict__ src,
+                                                           int64_t frags, uint32_t *sink)
+{
+    uint32_t a = 0;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < frags; i += 4 * stride) {
+        const uint4 x0 = src[i], x1 = src[i + stride], x2 = src[i + 2 * stride], x3 = src[i + 3 * stride];
+        a += (x0.x ^ x0.y ^ x0.z ^ x0.w) + (x1.x ^ x1.y ^ x1.z ^ x1.w) + (x2.x ^ x2.y ^ x2.z ^ x2.w) +
+             (x3.x ^ x3.y ^ x3.z ^ x3.w);
+    }
+    for (; i < frags; i += stride) {
+        const uint4 x = src[i];
+        a += x.x ^ x.y ^ x.z ^ x.w;
+    }
+    // a store that (almost) never happens keeps the loads alive without write traffic
+    if (a == 0x9e3779b9u) sink[blockIdx.x] = a;
+}
+
+// ---- host side -----------------------------------------------------------------
+int elem_bytes(pa_dtype dt) { return dt == PA_F32 ? 4 : 2; }
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool shape_supported(pa_dtype dt, int D, int B)
+{
+    if (dt != PA_F32 && dt != PA_F16 && dt != PA_BF16) return false;
+    if (D != 64 && D != 128) return false;
+    if (B != 8 && B != 16 && B != 32 && B != 64 && B != 128) return false;
+    const int lpt = D * elem_bytes(dt) / 16;   // lanes per token row
+    const int tpl = kWave / lpt;
+    return lpt >= 8 && lpt <= 32 && B % tpl == 0;
+}
+
+struct DecodeArgs {
+    void *out;
+    const void *q;
+    const char *k_cache, *v_cache;
+    const int32_t *block_tables;
+    int32_t max_blocks;
+    const int32_t *context_lens;
+    int32_t S, H;
+    float scale_log2;
+    int32_t partition_size, max_parts;
+    float *ws_acc, *ws_ml;
+    hipStream_t stream;
+};
+
+template <int DT, int D, int B, int W, int U, bool PART>
+void launch_decode(const DecodeArgs &a)
+{
+    const unsigned grid = (unsigned)((int64_t)a.S * a.H * (PART ? a.max_parts : 1));
+    hipLaunchKernelGGL((pa_decode_kernel<DT, D, B, W, U, PART>), dim3(grid), dim3(W * kWave), 0, a.stream,
+                       a.out, a.q, a.k_cache, a.v_cache, a.block_tables, a.max_blocks, a.context_lens,
+                       a.H, a.scale_log2, a.partition_size, a.max_parts, a.ws_acc, a.ws_ml);
+    if (PART)
+        hipLaunchKernelGGL((pa_reduce_kernel<DT, D>), dim3((unsigned)(a.S * a.H)), dim3(kWave), 0,
+                           a.stream, a.out, a.context_lens, a.H, a.partition_size, a.max_parts,
+                           a.ws_acc, a.ws_ml);
+}
+
+// waves per workgroup: one pass walks whole contexts, so more waves share an
+// item; a partition is short, so fewer do
+constexpr int kWavesSingle = 8;
+constexpr int kWavesPart = 4;
+// chunks requested together per trip of the steady-state loop
+constexpr int kChunksPerTrip = 2;
+
+template <int DT, int D, int B>
+void dispatch_mode(const DecodeArgs &a)
+{
+    if (a.partition_size > 0)
+        launch_decode<DT, D, B, kWavesPart, kChunksPerTrip, true>(a);
+    else
+        launch_decode<DT, D, B, kWavesSingle, kChunksPerTrip, false>(a);
+}
+
+template <int DT, int D>
+bool dispatch_block(const DecodeArgs &a, int B)
+{
+    switch (B) {
+    case 8: dispatch_mode<DT, D, 8>(a); return true;
+    case 16: dispatch_mode<DT, D, 16>(a); return true;
+    case 32: dispatch_mode<DT, D, 32>(a); return true;
+    case 64: dispatch_mode<DT, D, 64>(a); return true;
+    case 128: dispatch_mode<DT, D, 128>(a); return true;
+    }
+    return false;
+}
+
+bool dispatch_decode(const DecodeArgs &a, pa_dtype dt, int D, int B)
+{
+    if (dt == PA_F32 && D == 64) return dispatch_block<PA_F32, 64>(a, B);
+    if (dt == PA_F32 && D == 128) return dispatch_block<PA_F32, 128>(a, B);
+    if (dt == PA_F16 && D == 64) return dispatch_block<PA_F16, 64>(a, B);
+    if (dt == PA_F16 && D == 128) return dispatch_block<PA_F16, 128>(a, B);
+    if (dt == PA_BF16 && D == 64) return dispatch_block<PA_BF16, 64>(a, B);
+    if (dt == PA_BF16 && D == 128) return dispatch_block<PA_BF16, 128>(a, B);
+    return false;
+}
+
+int auto_partition(int max_context_len, int B)
+{
+    // short batches gain nothing from a split; otherwise 256-token ranges keep
+    // the work items uniform while the partial results stay < 1% of the traffic
+    int ps = 256;
+    if (ps % B) ps = ((ps + B - 1) / B) * B;
+    return max_context_len > ps ? ps : 0;
+}
+
+} // namespace
+
+extern "C" {
+
+int pa_version(void) { return 1; }
+
+const char *pa_status_string(pa_status st)
+{
+    switch (st) {
+    case PA_OK: return "ok";
+    case PA_ERR_NULL: return "null pointer";
+    case PA_ERR_SHAPE: return "bad shape or size";
+    case PA_ERR_UNSUPPORTED: return "unsupported dtype / head_dim / block_size";
+    case PA_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case PA_ERR_WORKSPACE: return "workspace missing or too small";
+    case PA_ERR_HIP: return "HIP runtime error";
+    case PA_ERR_INVALID: return "invalid index found by pa_debug_validate";
+    }
+    return "unknown status";
+}
+
+size_t pa_decode_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t head_dim,
+                                 int32_t block_size, int32_t max_context_len, int32_t partition_size)
+{
+    if (num_seqs <= 0 || num_heads <= 0 || head_dim <= 0 || block_size <= 0 || max_context_len <= 0) return 0;
+    if (partition_size == PA_PARTITION_AUTO) partition_size = auto_partition(max_context_len, block_size);
+    if (partition_size <= 0) return 0;
+    const size_t parts = (size_t)((max_context_len + partition_size - 1) / partition_size);
+    return (size_t)num_seqs * num_heads * parts * ((size_t)head_dim + 2) * sizeof(float);
+}
+
+pa_status pa_decode(void *out, const void *q, const void *k_cache, const void *v_cache,
+                    const int32_t *block_tables, int32_t max_blocks_per_seq,
+                    const int32_t *context_lens, int32_t num_seqs, int32_t num_heads,
+                    int32_t head_dim, int32_t block_size, int64_t num_blocks, pa_dtype dtype,
+                    float scale, int32_t max_context_len, int32_t partition_size, void *workspace,
+                    size_t workspace_bytes, void *stream)
+{
+    if (num_seqs < 0 || num_heads <= 0 || head_dim <= 0 || block_size <= 0 || num_blocks <= 0 ||
+        max_blocks_per_seq <= 0 || max_context_len < 0)
+        return PA_ERR_SHAPE;
+    if (!shape_supported(dtype, head_dim, block_size)) return PA_ERR_UNSUPPORTED;
+    if ((int64_t)max_context_len > (int64_t)max_blocks_per_seq * block_size) return PA_ERR_SHAPE;
+    if (partition_size < PA_PARTITION_AUTO) return PA_ERR_SHAPE;
+    if (partition_size > 0 && partition_size % block_size) return PA_ERR_SHAPE;
+    if (num_seqs == 0) return PA_OK;
+    if (!out || !q || !k_cache || !v_cache || !block_tables || !context_lens) return PA_ERR_NULL;
+    if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return PA_ERR_ALIGN;
+    if ((int64_t)num_seqs * num_heads > (int64_t)0x7fffffff / 64) return PA_ERR_SHAPE;
+
+    if (partition_size == PA_PARTITION_AUTO)
+        partition_size = workspace ? auto_partition(max_context_len, block_size) : 0;
+    if (partition_size >= max_context_len) partition_size = 0;   // one range: plain single pass
+
+    DecodeArgs a;
+    memset(&a, 0, sizeof(a));
+    a.out = out;
+    a.q = q;
+    a.k_cache = static_cast<const char *>(k_cache);
+    a.v_cache = static_cast<const char *>(v_cache);
+    a.block_tables = block_tables;
+    a.max_blocks = max_blocks_per_seq;
+    a.context_lens = context_lens;
+    a.S = num_seqs;
+    a.H = num_heads;
+    a.scale_log2 = scale * kLog2e;
+    a.partition_size = partition_size;
+    a.max_parts = 1;
+    a.stream = static_cast<hipStream_t>(stream);
+    if (partition_size > 0) {
+        a.max_parts = (max_context_len + partition_size - 1) / partition_size;
+        const size_t need = pa_decode_workspace_bytes(num_seqs, num_heads, head_dim, block_size,
+                                                      max_context_len, partition_size);
+        if (!workspace || workspace_bytes < need) return PA_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return PA_ERR_ALIGN;
+        if ((int64_t)num_seqs * num_heads * a.max_parts > 0x7fffffff) return PA_ERR_SHAPE;
+        a.ws_acc = static_cast<float *>(workspace);
+        a.ws_ml = a.ws_acc + (size_t)num_seqs * num_heads * a.max_parts * head_dim;
+    }
+    if (!dispatch_decode(a, dtype, head_dim, block_size)) return PA_ERR_UNSUPPORTED;
+    return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
+}
+
+pa_status pa_reshape_and_cache(const void *k, const void *v, void *k_cache, void *v_cache,
+                               const int64_t *slot_mapping, int32_t num_tokens, int32_t num_heads,
+                               int32_t head_dim, int32_t block_size, int64_t num_blocks,
+                               pa_dtype dtype, void *stream)
+{
+    if (num_tokens < 0 || num_heads <= 0 || head_dim <= 0 || block_size <= 0 || num_blocks <= 0)
+        return PA_ERR_SHAPE;
+    if (dtype != PA_F32 && dtype != PA_F16 && dtype != PA_BF16) return PA_ERR_UNSUPPORTED;
+    const int row_bytes = head_dim * elem_bytes(dtype);
+    if (row_bytes % 16) return PA_ERR_UNSUPPORTED;
+    if (num_tokens == 0) return PA_OK;
+    if (!k || !v || !k_cache || !v_cache || !slot_mapping) return PA_ERR_NULL;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(k_cache) || !aligned16(v_cache)) return PA_ERR_ALIGN;
+    const int32_t frags_per_row = row_bytes / 16;
+    const int64_t frags_per_token = (int64_t)frags_per_row * num_heads;
+    if (frags_per_token > 0x7fffffff) return PA_ERR_SHAPE;
+    const int64_t total = frags_per_token * num_tokens;
+    const int64_t groups = (total + 255) / 256;
+    if (groups > 0x7fffffff) return PA_ERR_SHAPE;
+    hipLaunchKernelGGL(reshape_and_cache_kernel, dim3((unsigned)groups, 2), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const uint4 *>(k),
+                       static_cast<const uint4 *>(v), static_cast<uint4 *>(k_cache),
+                       static_cast<uint4 *>(v_cache), slot_mapping, total, (int32_t)frags_per_token,
+                       frags_per_row, block_size);
+    return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
+}
+
+pa_status pa_copy_blocks(void *const *k_caches, void *const *v_caches, int32_t num_layers,
+                         const int64_t *src_dst_pairs, int32_t num_pairs, int32_t num_heads,
+                         int32_t head_dim, int32_t block_size, int64_t num_blocks, pa_dtype dtype,
+                         void *stream)
+{
+    if (num_layers <= 0 || num_pairs < 0 || num_heads <= 0 || head_dim <= 0 || block_size <= 0 ||
+        num_blocks <= 0)
+        return PA_ERR_SHAPE;
+    if (dtype != PA_F32 && dtype != PA_F16 && dtype != PA_BF16) return PA_ERR_UNSUPPORTED;
+    const int64_t block_bytes = (int64_t)num_heads * block_size * head_dim * elem_bytes(dtype);
+    if (block_bytes % 16) return PA_ERR_UNSUPPORTED;
+    if (num_pairs == 0) return PA_OK;
+    if (!k_caches || !v_caches || !src_dst_pairs) return PA_ERR_NULL;
+    if (num_pairs > 65535) return PA_ERR_SHAPE;
+    for (int l = 0; l < num_layers; ++l) {
+        if (!k_caches[l] || !v_caches[l]) return PA_ERR_NULL;
+        if (!aligned16(k_caches[l]) || !aligned16(v_caches[l])) return PA_ERR_ALIGN;
+    }
+    const int64_t frags = block_bytes / 16;
+    const unsigned slices = (unsigned)((frags + 1023) / 1024);
+    for (int l0 = 0; l0 < num_layers; l0 += kMaxCopyPtrs / 2) {
+        const int nl = num_layers - l0 < kMaxCopyPtrs / 2 ? num_layers - l0 : kMaxCopyPtrs / 2;
+        CachePtrs ptrs;
+        memset(&ptrs, 0, sizeof(ptrs));
+        for (int l = 0; l < nl; ++l) {
+            ptrs.p[2 * l] = static_cast<uint4 *>(k_caches[l0 + l]);
+            ptrs.p[2 * l + 1] = static_cast<uint4 *>(v_caches[l0 + l]);
+        }
+        hipLaunchKernelGGL(copy_blocks_kernel, dim3(slices, (unsigned)num_pairs, (unsigned)(2 * nl)),
+                           dim3(256), 0, static_cast<hipStream_t>(stream), ptrs, src_dst_pairs, frags);
+        if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
+    }
+    return PA_OK;
+}
+
+pa_status pa_debug_validate(const int32_t *block_tables, int32_t max_blocks_per_seq,
+                            const int32_t *context_lens, int32_t num_seqs, int32_t max_context_len,
+                            const int64_t *slot_mapping, int32_t num_tokens,
+                            const int64_t *src_dst_pairs, int32_t num_pairs, int32_t block_size,
+                            int64_t num_blocks, void *stream)
+{
+    if (block_size <= 0 || num_blocks <= 0 || num_seqs < 0 || num_tokens < 0 || num_pairs < 0)
+        return PA_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    pa_status result = PA_OK;
+    if (block_tables && context_lens && num_seqs > 0) {
+        if (max_blocks_per_seq <= 0) return PA_ERR_SHAPE;
+        const size_t nt = (size_t)num_seqs * max_blocks_per_seq;
+        int32_t *tab = static_cast<int32_t *>(malloc(nt * sizeof(int32_t)));
+        int32_t *len = static_cast<int32_t *>(malloc((size_t)num_seqs * sizeof(int32_t)));
+        if (!tab || !len) { free(tab); free(len); return PA_ERR_HIP; }
+        bool ok = hipMemcpyAsync(tab, block_tables, nt * sizeof(int32_t), hipMemcpyDeviceToHost, st) == hipSuccess &&
+                  hipMemcpyAsync(len, context_lens, (size_t)num_seqs * sizeof(int32_t), hipMemcpyDeviceToHost, st) == hipSuccess &&
+                  hipStreamSynchronize(st) == hipSuccess;
+        if (!ok) result = PA_ERR_HIP;
+        for (int s = 0; ok && s < num_seqs && result == PA_OK; ++s) {
+            const int64_t n = len[s];
+            if (n < 0 || n > max_context_len || n > (int64_t)max_blocks_per_seq * block_size) { result = PA_ERR_INVALID; break; }
+            const int64_t nb = (n + block_size - 1) / block_size;
+            for (int64_t j = 0; j < nb; ++j) {
+                const int64_t pb = tab[(size_t)s * max_blocks_per_seq + j];
+                if (pb < 0 || pb >= num_blocks) { result = PA_ERR_INVALID; break; }
+            }
+        }
+        free(tab);
+        free(len);
+        if (result != PA_OK) return result;
+    }
+    if (slot_mapping && num_tokens > 0) {
+        int64_t *sl = static_cast<int64_t *>(malloc((size_t)num_tokens * sizeof(int64_t)));
+        if (!sl) return PA_ERR_HIP;
+        bool ok = hipMemcpyAsync(sl, slot_mapping, (size_t)num_tokens * sizeof(int64_t), hipMemcpyDeviceToHost, st) == hipSuccess &&
+                  hipStreamSynchronize(st) == hipSuccess;
+        if (!ok) result = PA_ERR_HIP;
+        const int64_t total = num_blocks * block_size;
+        // duplicate detection with one bit per slot
+        uint8_t *seen = ok ? static_cast<uint8_t *>(calloc((size_t)(total + 7) / 8, 1)) : nullptr;
+        if (ok && !seen) result = PA_ERR_HIP;
+        for (int t = 0; seen && t < num_tokens; ++t) {
+            const int64_t x = sl[t];
+            if (x < 0) continue;
+            if (x >= total || (seen[x >> 3] >> (x & 7)) & 1) { result = PA_ERR_INVALID; break; }
+            seen[x >> 3] |= (uint8_t)(1u << (x & 7));
+        }
+        free(seen);
+        free(sl);
+        if (result != PA_OK) return result;
+    }
+    if (src_dst_pairs && num_pairs > 0) {
+        int64_t *pr = static_cast<int64_t *>(malloc((size_t)num_pairs * 2 * sizeof(int64_t)));
+        if (!pr) return PA_ERR_HIP;
+        bool ok = hipMemcpyAsync(pr, src_dst_pairs, (size_t)num_pairs * 2 * sizeof(int64_t), hipMemcpyDeviceToHost, st) == hipSuccess &&
+                  hipStreamSynchronize(st) == hipSuccess;
+        if (!ok) result = PA_ERR_HIP;
+        uint8_t *role = ok ? static_cast<uint8_t *>(calloc((size_t)num_blocks, 1)) : nullptr;   // 1 = src, 2 = dst
+        if (ok && !role) result = PA_ERR_HIP;
+        for (int i = 0; role && i < num_pairs && result == PA_OK; ++i) {
+            const int64_t src = pr[2 * i], dst = pr[2 * i + 1];
+            if (src < 0 || src >= num_blocks || dst < 0 || dst >= num_blocks) { result = PA_ERR_INVALID; break; }
+            if (role[dst] != 0 || role[src] == 2) { result = PA_ERR_INVALID; break; }
+            role[src] = 1;
+            role[dst] = 2;
+        }
+        free(role);
+        free(pr);
+    }
+    return result;
+}
+
+pa_status pa_stream_read(const void *src, size_t bytes, void *sink, void *stream)
+{
+    if (!src || !sink) return PA_ERR_NULL;
+    if (bytes == 0 || bytes % 16) return PA_ERR_SHAPE;
+    if (!aligned16(src)) return PA_ERR_ALIGN;
+    const int64_t frags = (int64_t)(bytes / 16);
+    int64_t groups = (frags + 256 * 16 - 1) / (256 * 16);   // 16 fragments per thread
+    if (groups > 65536) groups = 65536;
+    if (groups < 1) groups = 1;
+    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)groups), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const uint4 *>(src), frags,
+                       static_cast<uint32_t *>(sink));
+    return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
+}
+
+} // extern "C"

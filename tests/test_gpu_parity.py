@@ -1,0 +1,234 @@
+"""GPU parity: the HIP library against the fp64 CPU oracle, element by element, on
+the same seeded inputs.  Cache writes and block copies must match bit for bit;
+decode must stay within the stated max-abs tolerance (fp16 2e-3, bf16 1.6e-2,
+fp32 1e-5) of the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from harness import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pa():
+    import paper_2309_06180_amd as pa
+    pa.load_library()
+    return pa
+
+
+from gpu_util import (TOL, DeviceWorkload, gpu_cache_ops, gpu_decode, oracle_cache_ops,  # noqa: E402
+                      out_to_f64, same_bits, to_dev, to_np)
+
+
+def run_and_compare(pa, w, partitions=(0,), q_mult=1.0, seed=None, rows=None):
+    v = W.make_values(w, seed=seed, q_mult=q_mult)
+    dw = DeviceWorkload(w, v)
+    assert pa.pa_debug_validate(dw.block_tables, dw.context_lens, w.max_context_len, dw.write_slots,
+                                dw.copy_pairs, w.block_size, w.num_blocks) == 0
+    gpu_cache_ops(pa, dw)
+    torch.cuda.synchronize()
+    kc, vc = oracle_cache_ops(w, v)
+    assert same_bits(dw.k_cache, kc, w.dtype), "%s: K cache differs after copy/write" % w.name
+    assert same_bits(dw.v_cache, vc, w.dtype), "%s: V cache differs after copy/write" % w.name
+    ref = oracle.decode(v.q, kc, vc, w.block_tables, w.context_lens, w.scale, w.dtype, rows=rows)
+    errs = {}
+    for ps in partitions:
+        out = out_to_f64(gpu_decode(pa, dw, ps), w.dtype)
+        if rows is not None:
+            out = out[rows[:, 0], rows[:, 1]]
+        assert np.isfinite(out).all(), "%s ps=%d: non-finite output" % (w.name, ps)
+        errs[ps] = float(np.abs(out - ref).max())
+        assert errs[ps] <= TOL[w.dtype], "%s ps=%d: max abs err %g" % (w.name, ps, errs[ps])
+    return errs
+
+
+# ---------------------------------------------------------------------------
+def test_config1_tiny_fp32(pa):
+    print(run_and_compare(pa, W.config1(), partitions=(0, 16, 32, 64, pa.PA_PARTITION_AUTO)))
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_config2_reduced_fp16(pa, seed):
+    # several blocks per wave, ragged tails, 1..700 tokens
+    w = W.config2(seed=seed, num_seqs=24, max_len=700, H=5)
+    print(run_and_compare(pa, w, partitions=(0, 64, 256, 512, pa.PA_PARTITION_AUTO)))
+
+
+def test_config4_reduced_bf16(pa):
+    w = W.config4(num_seqs=20, H=3, median=400, cap=1100)
+    print(run_and_compare(pa, w, partitions=(0, 128, 512)))
+
+
+def test_config3_reduced_sharing(pa):
+    w = W.config3(num_groups=6, H=4, prompt_median=60, prompt_cap=300, max_out=90)
+    assert len(w.copy_pairs) > 0
+    print(run_and_compare(pa, w, partitions=(0, 64)))
+
+
+def test_config5_reduced_beam_one_layer(pa):
+    w = W.config5(num_seqs=14, H=4, min_len=100, max_len=700)
+    print(run_and_compare(pa, w, partitions=(0, 256)))
+
+
+@pytest.mark.parametrize("dtype,D,B", [("f16", 128, 16), ("f16", 128, 32), ("f16", 64, 16), ("f16", 64, 8),
+                                       ("bf16", 128, 16), ("bf16", 128, 32), ("bf16", 64, 32),
+                                       ("f32", 64, 16), ("f32", 128, 16), ("f32", 64, 32),
+                                       ("f16", 128, 8), ("f16", 128, 64), ("bf16", 128, 128)])
+def test_shape_matrix(pa, dtype, D, B):
+    rng = np.random.default_rng(D * 1000 + B)
+    lens = rng.integers(1, 6 * B + 40, size=9)
+    w = W.independent_sequences("matrix", dtype, 3, D, B, lens, seed=D + B)
+    ps = 2 * B if 2 * B >= 32 else 32
+    print(run_and_compare(pa, w, partitions=(0, ps)))
+
+
+def test_edge_context_lengths(pa):
+    # one below / at / one above every boundary the kernels have: block, chunk, partition
+    B, PS = 16, 64
+    lens = np.array([1, 2, 3, 4, 5, B - 1, B, B + 1, 2 * B - 1, 2 * B, 2 * B + 1, PS - 1, PS, PS + 1,
+                     2 * PS - 1, 2 * PS, 2 * PS + 1, 8 * PS, 8 * PS + 1, 1023, 1024, 1025], dtype=np.int64)
+    for dtype in ("f16", "bf16"):
+        w = W.independent_sequences("edges", dtype, 2, 128, B, lens, seed=5)
+        print(dtype, run_and_compare(pa, w, partitions=(0, PS, 256)))
+
+
+def test_empty_context_gives_zero_row(pa):
+    w = W.independent_sequences("zeros", "f16", 2, 128, 16, np.array([0, 40, 0, 300]), seed=6)
+    v = W.make_values(w)
+    dw = DeviceWorkload(w, v)
+    gpu_cache_ops(pa, dw)
+    kc, vc = oracle_cache_ops(w, v)
+    ref = oracle.decode(v.q, kc, vc, w.block_tables, w.context_lens, w.scale, w.dtype)
+    for ps in (0, 64):
+        out = out_to_f64(gpu_decode(pa, dw, ps), w.dtype)
+        assert not out[0].any() and not out[2].any()
+        assert np.abs(out - ref).max() <= TOL["f16"]
+
+
+def test_sharp_softmax(pa):
+    # queries scaled by 8: logits spread over tens of units, the running maximum moves a lot
+    w = W.config2(seed=9, num_seqs=12, max_len=600, H=4)
+    print(run_and_compare(pa, w, partitions=(0, 128), q_mult=8.0))
+
+
+def test_context_len_one_is_bit_exact(pa):
+    for dtype in ("f16", "bf16", "f32"):
+        D = 64 if dtype == "f32" else 128
+        w = W.independent_sequences("ones", dtype, 4, D, 16, np.ones(7, dtype=np.int64), seed=7)
+        v = W.make_values(w)
+        dw = DeviceWorkload(w, v)
+        gpu_cache_ops(pa, dw)
+        out = to_np(gpu_decode(pa, dw, 0), dtype)
+        want = v.v_new                                   # the only token of each sequence
+        assert np.array_equal(out.view(np.uint8), want.view(np.uint8))
+
+
+def test_deterministic_and_placement_invariant(pa):
+    w = W.config2(seed=11, num_seqs=10, max_len=500, H=4)
+    v = W.make_values(w)
+    dw = DeviceWorkload(w, v)
+    gpu_cache_ops(pa, dw)
+    for ps in (0, 128):
+        a = to_np(gpu_decode(pa, dw, ps), w.dtype)
+        b = to_np(gpu_decode(pa, dw, ps), w.dtype)
+        assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), "run-to-run difference"
+        # relabel physical blocks by a permutation, moving the data along (Sec. 4.1: placement is free)
+        perm = np.random.default_rng(3).permutation(w.num_blocks)
+        inv = np.argsort(perm)
+        kc2 = dw.k_cache[to_dev(inv)].contiguous()       # new block perm[i] holds old block i
+        vc2 = dw.v_cache[to_dev(inv)].contiguous()
+        bt = w.block_tables.copy()
+        B = w.block_size
+        for s in range(w.num_seqs):
+            nb = (int(w.context_lens[s]) + B - 1) // B
+            bt[s, :nb] = perm[bt[s, :nb]]
+        out = torch.empty_like(dw.q)
+        ws = torch.empty(max(1, pa.pa_decode_workspace_bytes(w.num_seqs, w.num_heads, w.head_dim, B,
+                                                            w.max_context_len, ps)), dtype=torch.uint8, device="cuda")
+        pa.pa_decode(out, dw.q, kc2, vc2, to_dev(bt), dw.context_lens, B, float(w.scale),
+                     w.max_context_len, ps, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(out, w.dtype).view(np.uint8), a.view(np.uint8)), "placement changed the bits"
+
+
+def test_reshape_and_cache_prefill_sized(pa):
+    # thousands of tokens in one call (a prompt phase storing its KV), with skipped padding tokens
+    rng = np.random.default_rng(21)
+    T, H, D, B, NB = 3000, 5, 128, 16, 400
+    for dtype in ("f16", "bf16", "f32"):
+        k = W.to_storage(rng.standard_normal((T, H, D)).astype(np.float32), dtype)
+        v = W.to_storage(rng.standard_normal((T, H, D)).astype(np.float32), dtype)
+        kc = W.to_storage(rng.standard_normal((NB, H, B, D)).astype(np.float32), dtype)
+        vc = W.to_storage(rng.standard_normal((NB, H, B, D)).astype(np.float32), dtype)
+        slots = rng.permutation(NB * B)[:T].astype(np.int64)
+        slots[rng.integers(0, T, size=40)] = -1
+        dk, dv = to_dev(kc, dtype), to_dev(vc, dtype)
+        pa.pa_reshape_and_cache(to_dev(k, dtype), to_dev(v, dtype), dk, dv, to_dev(slots))
+        torch.cuda.synchronize()
+        oracle.reshape_and_cache(k, v, kc, vc, slots, dtype)
+        assert same_bits(dk, kc, dtype) and same_bits(dv, vc, dtype)
+
+
+def test_copy_blocks_multi_layer_fan_out(pa):
+    rng = np.random.default_rng(22)
+    L, NB, H, B, D = 5, 40, 3, 16, 128
+    ks = [W.to_storage(rng.standard_normal((NB, H, B, D)).astype(np.float32), "bf16") for _ in range(L)]
+    vs = [W.to_storage(rng.standard_normal((NB, H, B, D)).astype(np.float32), "bf16") for _ in range(L)]
+    pairs = np.array([[1, 3], [7, 0], [7, 5], [7, 9], [39, 20], [2, 38]], dtype=np.int64)
+    dks, dvs = [to_dev(k, "bf16") for k in ks], [to_dev(v, "bf16") for v in vs]
+    pa.pa_copy_blocks(dks, dvs, to_dev(pairs))
+    pa.pa_copy_blocks(dks, dvs, to_dev(np.zeros((0, 2), dtype=np.int64)))    # empty list: no launch
+    torch.cuda.synchronize()
+    oracle.copy_blocks(ks, vs, pairs, "bf16")
+    for l in range(L):
+        assert same_bits(dks[l], ks[l], "bf16") and same_bits(dvs[l], vs[l], "bf16")
+
+
+def test_copy_blocks_many_layers_two_launches(pa):
+    # more layers than one launch carries pointers for
+    rng = np.random.default_rng(23)
+    L, NB, H, B, D = 70, 6, 1, 8, 64
+    ks = [W.to_storage(rng.standard_normal((NB, H, B, D)).astype(np.float32), "f16") for _ in range(L)]
+    vs = [W.to_storage(rng.standard_normal((NB, H, B, D)).astype(np.float32), "f16") for _ in range(L)]
+    pairs = np.array([[0, 4], [1, 5]], dtype=np.int64)
+    dks, dvs = [to_dev(k) for k in ks], [to_dev(v) for v in vs]
+    pa.pa_copy_blocks(dks, dvs, to_dev(pairs))
+    torch.cuda.synchronize()
+    oracle.copy_blocks(ks, vs, pairs, "f16")
+    for l in range(L):
+        assert same_bits(dks[l], ks[l], "f16") and same_bits(dvs[l], vs[l], "f16")
+
+
+def test_debug_validate_flags_bad_indices(pa):
+    w = W.config1()
+    bt, cl = to_dev(w.block_tables), to_dev(w.context_lens)
+    ok = pa.pa_debug_validate(bt, cl, w.max_context_len, to_dev(w.write_slots), None, w.block_size, w.num_blocks)
+    assert ok == 0
+    bad = w.block_tables.copy()
+    bad[0, 0] = w.num_blocks
+    assert pa.pa_debug_validate(to_dev(bad), cl, w.max_context_len, None, None, w.block_size, w.num_blocks) == 7
+    assert pa.pa_debug_validate(bt, cl, int(w.context_lens.max()) - 1, None, None, w.block_size, w.num_blocks) == 7
+    dup = w.write_slots.copy()
+    dup[1] = dup[0]
+    assert pa.pa_debug_validate(None, None, 0, to_dev(dup), None, w.block_size, w.num_blocks) == 7
+    pairs = np.array([[1, 2], [2, 3]], dtype=np.int64)          # a destination used as a source
+    assert pa.pa_debug_validate(None, None, 0, None, to_dev(pairs), w.block_size, w.num_blocks) == 7
+
+
+def test_workspace_and_argument_errors_on_device(pa):
+    w = W.config2(seed=1, num_seqs=4, max_len=300, H=2)
+    v = W.make_values(w)
+    dw = DeviceWorkload(w, v)
+    out = torch.empty_like(dw.q)
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(pa.PAError) as e:
+        pa.pa_decode(out, dw.q, dw.k_cache, dw.v_cache, dw.block_tables, dw.context_lens, w.block_size,
+                     float(w.scale), w.max_context_len, 64, small)
+    assert e.value.code == 5
+    with pytest.raises(pa.PAError) as e:
+        pa.pa_decode(out, dw.q, dw.k_cache, dw.v_cache, dw.block_tables, dw.context_lens, w.block_size,
+                     float(w.scale), w.max_context_len, 24, small)       # not a multiple of the block size
+    assert e.value.code == 2
