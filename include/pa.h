@@ -158,10 +158,11 @@ pa_status pa_debug_validate(const int32_t *block_tables, int32_t max_blocks_per_
                             int32_t block_size, int64_t num_blocks, void *stream);
 
 /*
- * pa_stream_read - bandwidth probe: sums `bytes` bytes (multiple of 16) at
- * `src` with 16-byte loads and writes one 4-byte word per workgroup to `sink`
- * (at least 4*65536 bytes).  Gives the streaming-read ceiling of the device
- * that roofline fractions are compared with.
+ * pa_stream_read - bandwidth probe: reads `bytes` bytes (multiple of 16) at
+ * `src` once with non-temporal 16-byte loads, one contiguous 256 KiB tile per
+ * workgroup, and (practically) never writes; `sink` must hold at least
+ * 4*65536 bytes.  Gives the streaming-read ceiling of the device that roofline
+ * fractions are put beside.
  */
 pa_status pa_stream_read(const void *src, size_t bytes, void *sink, void *stream);
 

@@ -162,9 +162,14 @@ template <> struct Traits<PA_BF16> {
     }
 };
 
-__device__ __forceinline__ uint4 load16(const char *p)
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+// 16-byte load with the non-temporal hint: K/V bytes are used exactly once per
+// call, and streaming them past the caches measurably raises the HBM rate.
+__device__ __forceinline__ uint4 load16_stream(const char *p)
 {
-    return *reinterpret_cast<const uint4 *>(p);
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
 }
 
 // ---- decode ----------------------------------------------------------------
@@ -246,9 +251,9 @@ __global__ __launch_bounds__(W *kWave) void pa_decode_kernel(
         const char *kp = k_cache + off + lane16;
         const char *vp = v_cache + off + lane16;
 #pragma unroll
-        for (int i = 0; i < LPC; ++i) ck.k[i] = load16(kp + i * 1024);
+        for (int i = 0; i < LPC; ++i) ck.k[i] = load16_stream(kp + i * 1024);
 #pragma unroll
-        for (int i = 0; i < LPC; ++i) ck.v[i] = load16(vp + i * 1024);
+        for (int i = 0; i < LPC; ++i) ck.v[i] = load16_stream(vp + i * 1024);
     };
     // MASK is set only for a chunk that may reach past t_end (the last one)
     auto consume = [&](Chunk &ck, int ci, auto mask_tag) {
@@ -487,24 +492,34 @@ __global__ __launch_bounds__(256) void copy_blocks_kernel(CachePtrs caches,
 }
 
 // ---- bandwidth probe ---------------------------------------------------------
-__global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restrict__ src,
+// Each workgroup streams one contiguous 256 KiB tile with non-temporal 16-byte
+// loads, eight in flight per thread: the access shape that reads fastest here.
+constexpr int kProbeTileFrags = 256 * 1024 / 16;
+__global__ __launch_bounds__(256) void stream_read_kernel(const char *__restrict__ src,
                                                            int64_t frags, uint32_t *sink)
 {
+    constexpr int U = 8;
+    const int64_t base = (int64_t)blockIdx.x * kProbeTileFrags;
     uint32_t a = 0;
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    for (; i + 3 * stride < frags; i += 4 * stride) {
-        const uint4 x0 = src[i], x1 = src[i + stride], x2 = src[i + 2 * stride], x3 = src[i + 3 * stride];
-        a += (x0.x ^ x0.y ^ x0.z ^ x0.w) + (x1.x ^ x1.y ^ x1.z ^ x1.w) + (x2.x ^ x2.y ^ x2.z ^ x2.w) +
-             (x3.x ^ x3.y ^ x3.z ^ x3.w);
-    }
-    for (; i < frags; i += stride) {
-        const uint4 x = src[i];
-        a += x.x ^ x.y ^ x.z ^ x.w;
+    for (int i = threadIdx.x; i < kProbeTileFrags; i += 256 * U) {
+        uint4 x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t f = base + i + u * 256;
+            x[u] = f < frags ? load16_stream(src + f * 16) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) a += x[u].x ^ x[u].y ^ x[u].z ^ x[u].w;
     }
     // a store that (almost) never happens keeps the loads alive without write traffic
-    if (a == 0x9e3779b9u) sink[blockIdx.x] = a;
+    if (a == 0x9e3779b9u) sink[blockIdx.x & 65535] = a;
 }
+
+// chunks requested together per trip of the steady-state loop
+#ifndef PA_CHUNKS_PER_TRIP
+#define PA_CHUNKS_PER_TRIP 2
+#endif
+constexpr int kChunksPerTrip = PA_CHUNKS_PER_TRIP;
 
 // ---- host side -----------------------------------------------------------------
 int elem_bytes(pa_dtype dt) { return dt == PA_F32 ? 4 : 2; }
@@ -531,37 +546,40 @@ struct DecodeArgs {
     int32_t S, H;
     float scale_log2;
     int32_t partition_size, max_parts;
+    int32_t waves;   // wavefronts per workgroup
     float *ws_acc, *ws_ml;
     hipStream_t stream;
 };
 
-template <int DT, int D, int B, int W, int U, bool PART>
+template <int DT, int D, int B, int W, bool PART>
 void launch_decode(const DecodeArgs &a)
 {
     const unsigned grid = (unsigned)((int64_t)a.S * a.H * (PART ? a.max_parts : 1));
-    hipLaunchKernelGGL((pa_decode_kernel<DT, D, B, W, U, PART>), dim3(grid), dim3(W * kWave), 0, a.stream,
-                       a.out, a.q, a.k_cache, a.v_cache, a.block_tables, a.max_blocks, a.context_lens,
-                       a.H, a.scale_log2, a.partition_size, a.max_parts, a.ws_acc, a.ws_ml);
+    hipLaunchKernelGGL((pa_decode_kernel<DT, D, B, W, kChunksPerTrip, PART>), dim3(grid), dim3(W * kWave), 0,
+                       a.stream, a.out, a.q, a.k_cache, a.v_cache, a.block_tables, a.max_blocks,
+                       a.context_lens, a.H, a.scale_log2, a.partition_size, a.max_parts, a.ws_acc, a.ws_ml);
     if (PART)
         hipLaunchKernelGGL((pa_reduce_kernel<DT, D>), dim3((unsigned)(a.S * a.H)), dim3(kWave), 0,
                            a.stream, a.out, a.context_lens, a.H, a.partition_size, a.max_parts,
                            a.ws_acc, a.ws_ml);
 }
 
-// waves per workgroup: one pass walks whole contexts, so more waves share an
-// item; a partition is short, so fewer do
-constexpr int kWavesSingle = 8;
-constexpr int kWavesPart = 4;
-// chunks requested together per trip of the steady-state loop
-constexpr int kChunksPerTrip = 2;
-
 template <int DT, int D, int B>
 void dispatch_mode(const DecodeArgs &a)
 {
-    if (a.partition_size > 0)
-        launch_decode<DT, D, B, kWavesPart, kChunksPerTrip, true>(a);
-    else
-        launch_decode<DT, D, B, kWavesSingle, kChunksPerTrip, false>(a);
+    if (a.partition_size > 0) {
+        if (a.waves >= 8)
+            launch_decode<DT, D, B, 8, true>(a);
+        else
+            launch_decode<DT, D, B, 4, true>(a);
+    } else {
+        switch (a.waves) {
+        case 2: launch_decode<DT, D, B, 2, false>(a); break;
+        case 4: launch_decode<DT, D, B, 4, false>(a); break;
+        case 8: launch_decode<DT, D, B, 8, false>(a); break;
+        default: launch_decode<DT, D, B, 16, false>(a); break;
+        }
+    }
 }
 
 template <int DT, int D>
@@ -588,13 +606,52 @@ bool dispatch_decode(const DecodeArgs &a, pa_dtype dt, int D, int B)
     return false;
 }
 
-int auto_partition(int max_context_len, int B)
+// ---- launch planning -----------------------------------------------------------
+// Measured on MI355X at the OPT-13B shape: a workgroup should have about one
+// wave per four chunks of its longest possible item - fewer waves leave the end
+// of the launch to a few slow workgroups, more waves cost launch time that
+// short items cannot pay back.  Splitting the context costs 3-8% (workspace
+// traffic, empty workgroups, the second kernel) and pays only when there are
+// too few (sequence, head) pairs to fill the compute units.
+int compute_units()
 {
-    // short batches gain nothing from a split; otherwise 256-token ranges keep
-    // the work items uniform while the partial results stay < 1% of the traffic
-    int ps = 256;
-    if (ps % B) ps = ((ps + B - 1) / B) * B;
-    return max_context_len > ps ? ps : 0;
+    static int cached = 0;
+    if (cached > 0) return cached;
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+        (void)hipGetLastError();
+        return 256;   // MI355X; not cached, so a later call with a device present asks again
+    }
+    cached = n;
+    return n;
+}
+
+int chunk_tokens(pa_dtype dt, int D, int B)
+{
+    const int tpl = kWave / (D * elem_bytes(dt) / 16);
+    const int lpc = B / tpl < 4 ? B / tpl : 4;
+    return lpc * tpl;
+}
+
+int waves_for(int tokens_per_item, int ct)
+{
+    const int chunks = (tokens_per_item + ct - 1) / ct;
+    if (chunks <= 4) return 2;
+    if (chunks <= 16) return 4;
+    if (chunks <= 32) return 8;
+    return 16;
+}
+
+int auto_partition(int S, int H, int max_context_len)
+{
+    const int cus = compute_units();
+    const int64_t items = (int64_t)S * H;
+    if (items >= 2 * (int64_t)cus || max_context_len <= 512) return 0;
+    const int64_t want_parts = (4 * (int64_t)cus + items - 1) / items;
+    int64_t ps = (max_context_len + want_parts - 1) / want_parts;
+    ps = ((ps + 255) / 256) * 256;   // a multiple of every supported block size
+    return ps >= max_context_len ? 0 : (int)ps;
 }
 
 } // namespace
@@ -622,8 +679,8 @@ size_t pa_decode_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t he
                                  int32_t block_size, int32_t max_context_len, int32_t partition_size)
 {
     if (num_seqs <= 0 || num_heads <= 0 || head_dim <= 0 || block_size <= 0 || max_context_len <= 0) return 0;
-    if (partition_size == PA_PARTITION_AUTO) partition_size = auto_partition(max_context_len, block_size);
-    if (partition_size <= 0) return 0;
+    if (partition_size == PA_PARTITION_AUTO) partition_size = auto_partition(num_seqs, num_heads, max_context_len);
+    if (partition_size <= 0 || partition_size >= max_context_len) return 0;
     const size_t parts = (size_t)((max_context_len + partition_size - 1) / partition_size);
     return (size_t)num_seqs * num_heads * parts * ((size_t)head_dim + 2) * sizeof(float);
 }
@@ -648,7 +705,7 @@ pa_status pa_decode(void *out, const void *q, const void *k_cache, const void *v
     if ((int64_t)num_seqs * num_heads > (int64_t)0x7fffffff / 64) return PA_ERR_SHAPE;
 
     if (partition_size == PA_PARTITION_AUTO)
-        partition_size = workspace ? auto_partition(max_context_len, block_size) : 0;
+        partition_size = workspace ? auto_partition(num_seqs, num_heads, max_context_len) : 0;
     if (partition_size >= max_context_len) partition_size = 0;   // one range: plain single pass
 
     DecodeArgs a;
@@ -665,6 +722,8 @@ pa_status pa_decode(void *out, const void *q, const void *k_cache, const void *v
     a.scale_log2 = scale * kLog2e;
     a.partition_size = partition_size;
     a.max_parts = 1;
+    a.waves = waves_for(partition_size > 0 ? partition_size : max_context_len,
+                        chunk_tokens(dtype, head_dim, block_size));
     a.stream = static_cast<hipStream_t>(stream);
     if (partition_size > 0) {
         a.max_parts = (max_context_len + partition_size - 1) / partition_size;
@@ -822,11 +881,10 @@ pa_status pa_stream_read(const void *src, size_t bytes, void *sink, void *stream
     if (bytes == 0 || bytes % 16) return PA_ERR_SHAPE;
     if (!aligned16(src)) return PA_ERR_ALIGN;
     const int64_t frags = (int64_t)(bytes / 16);
-    int64_t groups = (frags + 256 * 16 - 1) / (256 * 16);   // 16 fragments per thread
-    if (groups > 65536) groups = 65536;
-    if (groups < 1) groups = 1;
+    const int64_t groups = (frags + kProbeTileFrags - 1) / kProbeTileFrags;
+    if (groups > 0x7fffffff) return PA_ERR_SHAPE;
     hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)groups), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), static_cast<const uint4 *>(src), frags,
+                       static_cast<hipStream_t>(stream), static_cast<const char *>(src), frags,
                        static_cast<uint32_t *>(sink));
     return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
 }

@@ -85,6 +85,16 @@ def test_shape_matrix(pa, dtype, D, B):
     print(run_and_compare(pa, w, partitions=(0, ps)))
 
 
+@pytest.mark.parametrize("max_len", [40, 64, 200, 256, 400, 512, 1500])
+def test_every_workgroup_width(pa, max_len):
+    # the launch planner picks 2, 4, 8 or 16 waves per workgroup from max_context_len
+    rng = np.random.default_rng(max_len)
+    lens = np.concatenate([rng.integers(1, max_len + 1, size=10), [max_len, 1]])
+    for dtype in ("f16", "bf16"):
+        w = W.independent_sequences("widths", dtype, 3, 128, 16, lens, seed=max_len)
+        print(dtype, run_and_compare(pa, w, partitions=(0, 64, 512, 1024)))
+
+
 def test_edge_context_lengths(pa):
     # one below / at / one above every boundary the kernels have: block, chunk, partition
     B, PS = 16, 64
