@@ -43,6 +43,23 @@ def parse():
     return ap.parse_args()
 
 
+def profiled_traffic(workload_name):
+    """HBM bytes per pa_decode launch from the committed hardware-counter summary (FETCH_SIZE and
+    WRITE_SIZE passes of rocprofv3, scaled by a plain copy of known size), or None."""
+    path = os.path.join(ROOT, "profiles", "pa_decode_opt13b_hbm_traffic.md")
+    try:
+        kv = {}
+        for line in open(path):
+            if ":" in line and not line.startswith(("#", "|", " ")):
+                k, _, val = line.partition(":")
+                kv[k.strip()] = val.strip()
+        if kv.get("workload") == workload_name:
+            return int(kv["traffic_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        pass
+    return None
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -182,7 +199,8 @@ def main():
         "roofline": {"bound": "hbm", "achieved": algo_bytes / (decode_ms * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": algo_bytes / (decode_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                     "traffic": None, "kernel": "pa_decode_kernel",
+                     "traffic": profiled_traffic(w.name) if ps in (0, pa.PA_PARTITION_AUTO) else None,
+                     "kernel": "pa_decode_kernel",
                      "algorithmic_bytes_per_launch": algo_bytes},
     }
 

@@ -1,0 +1,126 @@
+"""GPU parity at the full sizes of the five configurations, in the launch configuration
+the benchmark uses (partition_size = the library's choice) and in the explicit split.
+
+Configs 2-4 are compared element by element over every (sequence, head) row.  Config 5
+(40 layers, ~140 GB of cache) is filled on the device with seeded normal values; three
+layers (first, middle, last) are copied back and checked in full."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from harness import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import (TOL, DeviceWorkload, gpu_cache_ops, gpu_decode, oracle_cache_ops,  # noqa: E402
+                      out_to_f64, same_bits, to_dev, to_np)
+
+
+@pytest.fixture(scope="module")
+def pa():
+    import paper_2309_06180_amd as pa
+    pa.load_library()
+    return pa
+
+
+def full_check(pa, w, partitions):
+    v = W.make_values(w)
+    dw = DeviceWorkload(w, v)
+    assert pa.pa_debug_validate(dw.block_tables, dw.context_lens, w.max_context_len, dw.write_slots,
+                                dw.copy_pairs, w.block_size, w.num_blocks) == 0
+    gpu_cache_ops(pa, dw)
+    torch.cuda.synchronize()
+    kc, vc = oracle_cache_ops(w, v)
+    assert same_bits(dw.k_cache, kc, w.dtype) and same_bits(dw.v_cache, vc, w.dtype)
+    ref = oracle.decode(v.q, kc, vc, w.block_tables, w.context_lens, w.scale, w.dtype)
+    errs = {}
+    for ps in partitions:
+        out = out_to_f64(gpu_decode(pa, dw, ps), w.dtype)
+        assert np.isfinite(out).all()
+        errs[ps] = float(np.abs(out - ref).max())
+        assert errs[ps] <= TOL[w.dtype], "%s ps=%d: max abs err %g" % (w.name, ps, errs[ps])
+    print(w.name, errs)
+    del dw
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(300)
+def test_config2_full(pa):
+    full_check(pa, W.config2(), (pa.PA_PARTITION_AUTO, 0, 512))
+
+
+@pytest.mark.timeout(300)
+def test_config3_full(pa):
+    w = W.config3()
+    assert w.num_seqs == 256 and len(w.copy_pairs) > 100 and len(w.write_slots) > 30000
+    full_check(pa, w, (pa.PA_PARTITION_AUTO, 256))
+
+
+@pytest.mark.timeout(300)
+def test_config4_full_single_and_split(pa):
+    full_check(pa, W.config4(), (0, 512))
+
+
+@pytest.mark.timeout(600)
+def test_config5_full_cache_beam_step(pa):
+    L = 40
+    w = W.config5()
+    S, H, D, B, NB = w.num_seqs, w.num_heads, w.head_dim, w.block_size, w.num_blocks
+    free, _ = torch.cuda.mem_get_info()
+    need = 2 * L * NB * H * B * D * 2
+    if free < need + (8 << 30):
+        pytest.skip("needs %.0f GB of free HBM" % (need / 1e9))
+    dev = torch.device("cuda")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    hole = to_dev(~w.init_filled)                                   # [NB][B], slots holding no token
+    ks, vs = [], []
+    for _ in range(L):
+        for lst in (ks, vs):
+            c = torch.randn((NB, H, B, D), device=dev, dtype=torch.bfloat16, generator=gen)
+            c.transpose(1, 2)[hole] = float("nan")
+            lst.append(c)
+    q = torch.randn((S, H, D), device=dev, dtype=torch.bfloat16, generator=gen)
+    k_new = [torch.randn((S, H, D), device=dev, dtype=torch.bfloat16, generator=gen) for _ in range(L)]
+    v_new = [torch.randn((S, H, D), device=dev, dtype=torch.bfloat16, generator=gen) for _ in range(L)]
+    bt, cl = to_dev(w.block_tables), to_dev(w.context_lens)
+    slots, pairs = to_dev(w.write_slots), to_dev(w.copy_pairs)
+    assert len(w.write_slots) == S and len(w.copy_pairs) > 0
+    assert pa.pa_debug_validate(bt, cl, w.max_context_len, slots, pairs, B, NB) == 0
+    sample = [0, L // 2, L - 1]
+    before = {l: (to_np(ks[l], "bf16").copy(), to_np(vs[l], "bf16").copy()) for l in sample}
+
+    # the step: copy-on-write for all layers at once, then per layer write + attention
+    pa.pa_copy_blocks(ks, vs, pairs)
+    outs = []
+    ws = torch.empty(max(16, pa.pa_decode_workspace_bytes(S, H, D, B, w.max_context_len, pa.PA_PARTITION_AUTO)),
+                     dtype=torch.uint8, device=dev)
+    for l in range(L):
+        pa.pa_reshape_and_cache(k_new[l], v_new[l], ks[l], vs[l], slots)
+        out = torch.empty_like(q)
+        pa.pa_decode(out, q, ks[l], vs[l], bt, cl, B, float(w.scale), w.max_context_len,
+                     pa.PA_PARTITION_AUTO, ws)
+        outs.append(out)
+    torch.cuda.synchronize()
+
+    qn = to_np(q, "bf16")
+    worst = 0.0
+    for l in sample:
+        kc, vc = before[l]
+        oracle.copy_blocks([kc], [vc], w.copy_pairs, "bf16")
+        oracle.reshape_and_cache(to_np(k_new[l], "bf16"), to_np(v_new[l], "bf16"), kc, vc, w.write_slots, "bf16")
+        assert same_bits(ks[l], kc, "bf16") and same_bits(vs[l], vc, "bf16"), "layer %d cache differs" % l
+        ref = oracle.decode(qn, kc, vc, w.block_tables, w.context_lens, w.scale, "bf16")
+        got = out_to_f64(outs[l], "bf16")
+        assert np.isfinite(got).all()
+        worst = max(worst, float(np.abs(got - ref).max()))
+        assert worst <= TOL["bf16"], "layer %d: max abs err %g" % (l, worst)
+        before[l] = None
+    # layers that were not copied back: finite everywhere, and different layers differ
+    for l in range(L):
+        assert torch.isfinite(outs[l].float()).all()
+    assert not torch.equal(outs[1], outs[2])
+    print("cfg5 full: %d blocks, %.0f GB cache, %d copy pairs, worst err %.3g" % (NB, need / 1e9, len(w.copy_pairs), worst))
+    del ks, vs
+    torch.cuda.empty_cache()
