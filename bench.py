@@ -31,7 +31,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"],
+                    help="cfg5 runs one of its 40 layers")
+    ap.add_argument("--decode", default="plain", choices=["plain", "shared"],
+                    help="shared: pa_decode_shared (blocks common to neighbouring sequences read once)")
     ap.add_argument("--partition", type=int, default=None,
                     help="partition_size for pa_decode (0 = one pass, -1 = library's choice); "
                          "default: the library's choice")
@@ -80,7 +83,8 @@ def main():
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
 
-    make = {"cfg1": W.config1, "cfg2": W.config2, "cfg3": W.config3, "cfg4": W.config4}[args.workload]
+    make = {"cfg1": W.config1, "cfg2": W.config2, "cfg3": W.config3, "cfg4": W.config4,
+            "cfg5": W.config5}[args.workload]
     w = make()
     v = W.make_values(w)
     # bring the cache to the state just before the step: everything but each
@@ -114,11 +118,16 @@ def main():
     S, H, D = w.num_seqs, w.num_heads, w.head_dim
     mcl = w.max_context_len
     ps = pa.PA_PARTITION_AUTO if args.partition is None else args.partition
-    ws_bytes = pa.pa_decode_workspace_bytes(S, H, D, B, mcl, ps)
+    shared = args.decode == "shared"
+    ws_bytes = pa.pa_decode_shared_workspace_bytes(S, H, D) if shared else \
+        pa.pa_decode_workspace_bytes(S, H, D, B, mcl, ps)
     d_ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
 
     def decode():
-        pa.pa_decode(d_out, d_q, d_kc, d_vc, d_bt, d_cl, B, float(w.scale), mcl, ps, d_ws)
+        if shared:
+            pa.pa_decode_shared(d_out, d_q, d_kc, d_vc, d_bt, d_cl, B, float(w.scale), mcl, d_ws)
+        else:
+            pa.pa_decode(d_out, d_q, d_kc, d_vc, d_bt, d_cl, B, float(w.scale), mcl, ps, d_ws)
 
     def step():
         pa.pa_copy_blocks([d_kc], [d_vc], d_pairs)
@@ -190,7 +199,8 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "num_seqs": S, "num_heads": H, "head_dim": D, "block_size": B,
                    "num_blocks": w.num_blocks, "context_tokens": int(w.context_lens.sum()),
-                   "max_context_len": mcl, "partition_size": ps, "seed": w.seed,
+                   "max_context_len": mcl, "partition_size": ps, "seed": w.seed, "decode": args.decode,
+                   "kv_bytes_logical": kv_bytes, "kv_bytes_unique": kv_unique,
                    "step": "copy_blocks(0 pairs)+reshape_and_cache(T=S)+pa_decode"},
         "query_tokens_per_s": S / (ms_per_step * 1e-3),
         "pct_of_hbm_peak": 100.0 * kv_unique / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
@@ -199,7 +209,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": algo_bytes / (decode_ms * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": algo_bytes / (decode_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                     "traffic": profiled_traffic(w.name) if ps in (0, pa.PA_PARTITION_AUTO) else None,
+                     "traffic": profiled_traffic(w.name) if ps in (0, pa.PA_PARTITION_AUTO) and not shared else None,
                      "kernel": "pa_decode_kernel",
                      "algorithmic_bytes_per_launch": algo_bytes},
     }

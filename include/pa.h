@@ -85,8 +85,8 @@ typedef enum { PA_F32 = 0, PA_F16 = 1, PA_BF16 = 2 } pa_dtype;
  *   partition_size   0: one pass per (sequence, head).
  *                    > 0, multiple of B: split-context - every (sequence, head)
  *                    is cut into ranges of partition_size tokens processed
- *                    independently (max logit, exp-sum and normalised partial
- *                    output kept in fp32 in the workspace), then a second
+ *                    independently (max logit, exp-sum and unnormalised partial
+ *                    sums kept in fp32 in the workspace), then a second
  *                    kernel merges them with the log-sum-exp rule.
  *                    PA_PARTITION_AUTO: the library picks a partition size
  *                    from the shape; falls back to one pass when workspace is
@@ -107,6 +107,32 @@ pa_status pa_decode(void *out, const void *q, const void *k_cache, const void *v
 size_t pa_decode_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t head_dim,
                                  int32_t block_size, int32_t max_context_len,
                                  int32_t partition_size);
+
+/*
+ * pa_decode_shared - pa_decode for batches whose sequences share physical
+ * blocks (Sec. 4.4: samples of one prompt and beams of one search map their
+ * common logical blocks to the same physical blocks).  Same arguments, same
+ * result as pa_decode; the difference is traffic.  The library compares the
+ * block tables of consecutive sequences on the device, groups up to 4
+ * neighbours whose tables start with the same full blocks, reads that common
+ * prefix once per group while applying it to every member's query, reads
+ * each sequence's remaining tokens separately, and merges the two partial
+ * results per sequence with the log-sum-exp rule (the split-context merge).
+ * Sequences that share nothing are handled as groups of one.
+ *
+ * Callers should place sequences that were forked from one another next to
+ * each other in the batch; any order is correct, only adjacent sharing is
+ * exploited.  `workspace` must hold pa_decode_shared_workspace_bytes(...)
+ * bytes.  Four kernels are enqueued on `stream`.
+ */
+pa_status pa_decode_shared(void *out, const void *q, const void *k_cache, const void *v_cache,
+                           const int32_t *block_tables, int32_t max_blocks_per_seq,
+                           const int32_t *context_lens, int32_t num_seqs, int32_t num_heads,
+                           int32_t head_dim, int32_t block_size, int64_t num_blocks,
+                           pa_dtype dtype, float scale, int32_t max_context_len, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
+size_t pa_decode_shared_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t head_dim);
 
 /*
  * pa_reshape_and_cache - store new K/V vectors into the paged cache

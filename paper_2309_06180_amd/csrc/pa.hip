@@ -68,6 +68,7 @@ template <int DT> struct Traits;
 
 template <> struct Traits<PA_F32> {
     static constexpr int E = 4, EPL = 4;
+    static constexpr bool FENCE_AXPY = false;
     static __device__ __forceinline__ float dot(const uint4 &k, const uint4 &q, float acc)
     {
         acc = __builtin_fmaf(as_f32(k.x), as_f32(q.x), acc);
@@ -91,6 +92,7 @@ template <> struct Traits<PA_F32> {
 
 template <> struct Traits<PA_F16> {
     static constexpr int E = 2, EPL = 8;
+    static constexpr bool FENCE_AXPY = false;
     static __device__ __forceinline__ float dot(const uint4 &k, const uint4 &q, float acc)
     {
         // products of two halves are exact in fp32; accumulation is fp32
@@ -128,6 +130,7 @@ template <> struct Traits<PA_F16> {
 
 template <> struct Traits<PA_BF16> {
     static constexpr int E = 2, EPL = 8;
+    static constexpr bool FENCE_AXPY = true;
     static __device__ __forceinline__ float dot(const uint4 &k, const uint4 &q, float acc)
     {
         acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.x), __builtin_bit_cast(bf16x2_t, q.x), acc, false);
@@ -168,12 +171,30 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 // call, and streaming them past the caches measurably raises the HBM rate.
 __device__ __forceinline__ uint4 load16_stream(const char *p)
 {
+#ifdef PA_PLAIN_LOADS
+    return *reinterpret_cast<const uint4 *>(p);
+#endif
     const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// Streaming copies: data that passes through once is loaded and stored with
+// the non-temporal hint (measured 6.4 TB/s of read+write traffic for block
+// copies against 5.7 TB/s with plain accesses).
+__device__ __forceinline__ u32x4_t load_frag_stream(const uint4 *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+}
+__device__ __forceinline__ void store_frag_stream(uint4 *p, u32x4_t v)
+{
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t *>(p));
+}
+
 // ---- decode ----------------------------------------------------------------
-// One workgroup of W wavefronts serves one (sequence, head[, partition]).
+// One workgroup of W wavefronts serves one work item: a (sequence, head) over
+// its whole context, over one fixed-size partition of it, or over the suffix
+// that follows a shared prefix; or a (group of sequences, head) over the
+// prefix of physical blocks the group has in common.
 //
 // Lane roles: a token row is LPT = D*E/16 lanes wide, so one 1 KiB wavefront
 // load covers TPL = 64/LPT consecutive tokens; lane = g*LPT + c holds
@@ -188,12 +209,53 @@ __device__ __forceinline__ uint4 load16_stream(const char *p)
 // the end with the log-sum-exp rule, so the inner loop has no cross-group
 // traffic.  Summation order depends only on logical token positions, so the
 // result does not change with the physical placement of blocks.
-template <int DT, int D, int B, int W, int U, bool PART>
-__global__ __launch_bounds__(W *kWave) void pa_decode_kernel(
-    void *__restrict__ out, const void *__restrict__ q, const char *__restrict__ k_cache,
-    const char *__restrict__ v_cache, const int32_t *__restrict__ block_tables, int32_t max_blocks,
-    const int32_t *__restrict__ context_lens, int32_t H, float scale_log2, int32_t partition_size,
-    int32_t max_parts, float *__restrict__ ws_acc, float *__restrict__ ws_ml)
+//
+// In the shared-prefix mode the workgroup holds the queries of up to G
+// sequences and applies every K/V fragment it loads to all of them, so blocks
+// that several sequences map (parallel sampling, beam search: Sec. 4.4) are
+// read from memory once per group instead of once per sequence.
+enum DecodeMode {
+    MODE_SINGLE = 0,   // whole context, writes the output row
+    MODE_PART = 1,     // tokens [part*PS, (part+1)*PS), writes partial `part` of max_parts
+    MODE_SUFFIX = 2,   // tokens [range_begin[s], n), writes partial 1 of 2
+    MODE_PREFIX = 3    // tokens [0, prefix) of a group, writes partial 0 of 2 for every member
+};
+
+struct DecodeParams {
+    void *out;
+    const void *q;
+    const char *k_cache, *v_cache;
+    const int32_t *block_tables;
+    const int32_t *context_lens;
+    const int32_t *ginfo;   // group table built by find_groups_kernel (shared-prefix path)
+    float *ws_acc, *ws_ml;
+    int32_t max_blocks, S, H;
+    int32_t partition_size, max_parts;
+    float scale_log2;
+};
+
+// Layout of the group table: [0] = number of groups, then five arrays of S
+// entries: range_begin[s] (tokens of s covered by its group's shared prefix),
+// group_start[g], group_size[g], group_prefix_tokens[g], and adj[s] (leading
+// blocks that s has in common with s-1; scratch of the discovery kernel).
+__device__ __host__ __forceinline__ int ginfo_range_begin(int S, int s) { (void)S; return 4 + s; }
+__device__ __host__ __forceinline__ int ginfo_group_start(int S, int g) { return 4 + S + g; }
+__device__ __host__ __forceinline__ int ginfo_group_size(int S, int g) { return 4 + 2 * S + g; }
+__device__ __host__ __forceinline__ int ginfo_group_prefix(int S, int g) { return 4 + 3 * S + g; }
+__device__ __host__ __forceinline__ int ginfo_adj(int S, int s) { return 4 + 4 * S + s; }
+__device__ __host__ __forceinline__ size_t ginfo_words(int S) { return 4 + 5 * (size_t)S; }
+
+#ifdef PA_TUNE_OCC
+#define PA_OCC_ATTR __attribute__((amdgpu_waves_per_eu(PA_TUNE_OCC, PA_TUNE_OCC)))
+#else
+// A sixteen-wave workgroup is kept alone on its compute unit (at most 7 waves
+// per SIMD, so a second one does not fit): measured on batches of mixed
+// lengths, two resident workgroups each run at half speed and stretch the end
+// of the launch by more than their overlap gains.
+#define PA_OCC_ATTR __attribute__((amdgpu_waves_per_eu(W == 16 ? 4 : 1, W == 16 ? 7 : 8)))
+#endif
+template <int DT, int D, int B, int W, int U, int MODE, int G>
+__global__ __launch_bounds__(W *kWave) PA_OCC_ATTR void pa_decode_kernel(const DecodeParams P)
 {
     using Tr = Traits<DT>;
     constexpr int E = Tr::E, EPL = Tr::EPL;
@@ -204,38 +266,71 @@ __global__ __launch_bounds__(W *kWave) void pa_decode_kernel(
     constexpr int CT = LPC * TPL;
     constexpr int64_t TILE_BYTES = (int64_t)B * ROW_BYTES;
     static_assert(LPT >= 8 && LPT <= 32 && B % TPL == 0 && B % CT == 0 && LPC >= 1, "shape");
+    static_assert(G == 1 || MODE == MODE_PREFIX, "several queries only in the shared-prefix mode");
 
     const int lane = threadIdx.x & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int g = lane / LPT;
     const int c = lane % LPT;
     const uint32_t lane16 = (uint32_t)lane * 16u;
+    const int H = P.H;
 
     int item = blockIdx.x;
     const int h = item % H;
     item /= H;
-    const int part = PART ? item % max_parts : 0;
-    const int s = PART ? item / max_parts : item;
 
-    const int n = context_lens[s];
-    const int t_begin = PART ? part * partition_size : 0;
-    const int t_end = PART ? (t_begin + partition_size < n ? t_begin + partition_size : n) : n;
+    // s: the sequence whose block table is walked; members: query slots in use
+    int s, part = 0, parts_stride = 1, t_begin = 0, t_end, members = 1;
+    if (MODE == MODE_PREFIX) {
+        if (item >= P.ginfo[0]) return;
+        s = P.ginfo[ginfo_group_start(P.S, item)];
+        members = P.ginfo[ginfo_group_size(P.S, item)];
+        t_end = P.ginfo[ginfo_group_prefix(P.S, item)];
+        parts_stride = 2;
+        if (members < 2) return;
+    } else if (MODE == MODE_SUFFIX) {
+        s = item;
+        t_begin = P.ginfo[ginfo_range_begin(P.S, s)];
+        t_end = P.context_lens[s];
+        part = 1;
+        parts_stride = 2;
+    } else if (MODE == MODE_PART) {
+        part = item % P.max_parts;
+        s = item / P.max_parts;
+        parts_stride = P.max_parts;
+        const int n = P.context_lens[s];
+        t_begin = part * P.partition_size;
+        t_end = t_begin + P.partition_size < n ? t_begin + P.partition_size : n;
+    } else {
+        s = item;
+        t_end = P.context_lens[s];
+    }
     if (t_begin >= t_end) {
-        if (!PART && w == 0 && g == 0) {
+        if (MODE == MODE_SINGLE && w == 0 && g == 0) {
             // empty context: zero row
-            reinterpret_cast<uint4 *>(out)[((int64_t)s * H + h) * LPT + c] = make_uint4(0, 0, 0, 0);
+            reinterpret_cast<uint4 *>(P.out)[((int64_t)s * H + h) * LPT + c] = make_uint4(0, 0, 0, 0);
         }
         return;
     }
 
-    const uint4 qf = reinterpret_cast<const uint4 *>(q)[((int64_t)s * H + h) * LPT + c];
-    const int32_t *__restrict__ table = block_tables + (int64_t)s * max_blocks;
+    // members of a group are consecutive sequences s, s+1, ...
+    uint4 qf[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        const int sj = j < members ? s + j : s;
+        qf[j] = reinterpret_cast<const uint4 *>(P.q)[((int64_t)sj * H + h) * LPT + c];
+    }
+    const int32_t *__restrict__ table = P.block_tables + (int64_t)s * P.max_blocks;
     const int nchunks = (t_end - t_begin + CT - 1) / CT;
 
-    float m = kNegBig, l = 0.f;
-    float acc[EPL];
+    float m[G], l[G], acc[G][EPL];
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+    for (int j = 0; j < G; ++j) {
+        m[j] = kNegBig;
+        l[j] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[j][e] = 0.f;
+    }
 
     struct Chunk {
         uint4 k[LPC], v[LPC];
@@ -248,8 +343,8 @@ __global__ __launch_bounds__(W *kWave) void pa_decode_kernel(
     auto issue = [&](Chunk &ck, int ci, int pb) {
         const int t0 = t_begin + ci * CT;
         const int64_t off = ((int64_t)pb * H + h) * TILE_BYTES + (int64_t)(t0 % B) * ROW_BYTES;
-        const char *kp = k_cache + off + lane16;
-        const char *vp = v_cache + off + lane16;
+        const char *kp = P.k_cache + off + lane16;
+        const char *vp = P.v_cache + off + lane16;
 #pragma unroll
         for (int i = 0; i < LPC; ++i) ck.k[i] = load16_stream(kp + i * 1024);
 #pragma unroll
@@ -259,38 +354,52 @@ __global__ __launch_bounds__(W *kWave) void pa_decode_kernel(
     auto consume = [&](Chunk &ck, int ci, auto mask_tag) {
         constexpr bool MASK = decltype(mask_tag)::value;
         const int t0 = t_begin + ci * CT;
-        float x[LPC];
-#pragma unroll
-        for (int i = 0; i < LPC; ++i) x[i] = group_sum<LPT>(Tr::dot(ck.k[i], qf, 0.f)) * scale_log2;
         if (MASK) {
             // slots at or past t_end hold no token and may contain anything, NaN
             // included - select them away, never multiply
 #pragma unroll
             for (int i = 0; i < LPC; ++i) {
                 const bool dead = t0 + i * TPL + g >= t_end;
-                x[i] = dead ? -INFINITY : x[i];
                 ck.v[i].x = dead ? 0u : ck.v[i].x;
                 ck.v[i].y = dead ? 0u : ck.v[i].y;
                 ck.v[i].z = dead ? 0u : ck.v[i].z;
                 ck.v[i].w = dead ? 0u : ck.v[i].w;
             }
         }
-        float m_new = m;
 #pragma unroll
-        for (int i = 0; i < LPC; ++i) m_new = fmaxf(m_new, x[i]);
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-        float p[LPC], psum = 0.f;
+        for (int j = 0; j < G; ++j) {
+            if (G > 1 && j >= members) break;
+            float x[LPC];
 #pragma unroll
-        for (int i = 0; i < LPC; ++i) {
-            p[i] = __builtin_amdgcn_exp2f(x[i] - m_new);
-            psum += p[i];
+            for (int i = 0; i < LPC; ++i) x[i] = group_sum<LPT>(Tr::dot(ck.k[i], qf[j], 0.f)) * P.scale_log2;
+            if (MASK) {
+#pragma unroll
+                for (int i = 0; i < LPC; ++i) x[i] = (t0 + i * TPL + g >= t_end) ? -INFINITY : x[i];
+            }
+            float m_new = m[j];
+#pragma unroll
+            for (int i = 0; i < LPC; ++i) m_new = fmaxf(m_new, x[i]);
+            const float alpha = __builtin_amdgcn_exp2f(m[j] - m_new);
+            float p[LPC], psum = 0.f;
+#pragma unroll
+            for (int i = 0; i < LPC; ++i) {
+                p[i] = __builtin_amdgcn_exp2f(x[i] - m_new);
+                psum += p[i];
+            }
+            l[j] = l[j] * alpha + psum;
+            m[j] = m_new;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[j][e] *= alpha;
+#pragma unroll
+            for (int i = 0; i < LPC; ++i) {
+                Tr::axpy(acc[j], p[i], ck.v[i]);
+                // bf16 widening is two VALU ops per pair; without a fence the
+                // scheduler widens every fragment first and doubles the live registers
+                if (Tr::FENCE_AXPY) __builtin_amdgcn_sched_barrier(0);
+            }
+            // one member at a time: interleaving their arithmetic multiplies the live registers
+            if (G > 1) __builtin_amdgcn_sched_barrier(0);
         }
-        l = l * alpha + psum;
-        m = m_new;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] *= alpha;
-#pragma unroll
-        for (int i = 0; i < LPC; ++i) Tr::axpy(acc, p[i], ck.v[i]);
     };
     const std::false_type full{};
     const std::true_type masked{};
@@ -321,102 +430,126 @@ __global__ __launch_bounds__(W *kWave) void pa_decode_kernel(
     }
 
     // merge the TPL token groups of this wave (lanes with equal c)
-    {
-        float M = m;
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        float M = m[j];
 #pragma unroll
         for (int d = LPT; d < kWave; d <<= 1) M = fmaxf(M, __shfl_xor(M, d));
-        const float f = __builtin_amdgcn_exp2f(m - M);
-        l *= f;
+        const float f = __builtin_amdgcn_exp2f(m[j] - M);
+        l[j] *= f;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] *= f;
+        for (int e = 0; e < EPL; ++e) acc[j][e] *= f;
 #pragma unroll
         for (int d = LPT; d < kWave; d <<= 1) {
-            l += __shfl_xor(l, d);
+            l[j] += __shfl_xor(l[j], d);
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], d);
+            for (int e = 0; e < EPL; ++e) acc[j][e] += __shfl_xor(acc[j][e], d);
         }
-        m = M;
+        m[j] = M;
     }
 
     // merge the W waves of the workgroup through LDS
     if (W > 1) {
-        __shared__ float sm_acc[W][D];
-        __shared__ float sm_m[W], sm_l[W];
+        __shared__ float sm_acc[W][G][D];
+        __shared__ float sm_m[W][G], sm_l[W][G];
         if (g == 0) {
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) sm_acc[w][c * EPL + e] = acc[e];
-            if (c == 0) {
-                sm_m[w] = m;
-                sm_l[w] = l;
+            for (int j = 0; j < G; ++j) {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) sm_acc[w][j][c * EPL + e] = acc[j][e];
+                if (c == 0) {
+                    sm_m[w][j] = m[j];
+                    sm_l[w][j] = l[j];
+                }
             }
         }
         __syncthreads();
         if (w != 0) return;
-        float M = sm_m[0];
 #pragma unroll
-        for (int i = 1; i < W; ++i) M = fmaxf(M, sm_m[i]);
-        l = 0.f;
+        for (int j = 0; j < G; ++j) {
+            float M = sm_m[0][j];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+            for (int i = 1; i < W; ++i) M = fmaxf(M, sm_m[i][j]);
+            l[j] = 0.f;
 #pragma unroll
-        for (int i = 0; i < W; ++i) {
-            const float f = __builtin_amdgcn_exp2f(sm_m[i] - M);
-            l = __builtin_fmaf(sm_l[i], f, l);
+            for (int e = 0; e < EPL; ++e) acc[j][e] = 0.f;
+            // (not fully unrolled: sixteen waves' worth of LDS reads hoisted at once would spill)
+#pragma unroll 2
+            for (int i = 0; i < W; ++i) {
+                const float f = __builtin_amdgcn_exp2f(sm_m[i][j] - M);
+                l[j] = __builtin_fmaf(sm_l[i][j], f, l[j]);
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[e] = __builtin_fmaf(sm_acc[i][c * EPL + e], f, acc[e]);
+                for (int e = 0; e < EPL; ++e)
+                    acc[j][e] = __builtin_fmaf(sm_acc[i][j][c * EPL + e], f, acc[j][e]);
+            }
+            m[j] = M;
         }
-        m = M;
     }
     if (g != 0) return;
 
-    if (PART) {
-        // unnormalised partial: the reduce kernel divides once
-        const int64_t slot = ((int64_t)s * H + h) * max_parts + part;
-        float *dst = ws_acc + slot * D + c * EPL;
+    if (MODE == MODE_SINGLE) {
+        const float inv = 1.0f / l[0];
 #pragma unroll
-        for (int e = 0; e < EPL; e += 4)
-            *reinterpret_cast<float4 *>(dst + e) = make_float4(acc[e], acc[e + 1], acc[e + 2], acc[e + 3]);
-        if (c == 0) *reinterpret_cast<float2 *>(ws_ml + slot * 2) = make_float2(m, l);
+        for (int e = 0; e < EPL; ++e) acc[0][e] *= inv;
+        reinterpret_cast<uint4 *>(P.out)[((int64_t)s * H + h) * LPT + c] = Tr::pack(acc[0]);
     } else {
-        const float inv = 1.0f / l;
+        // unnormalised partials: the reduce kernel divides once
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] *= inv;
-        reinterpret_cast<uint4 *>(out)[((int64_t)s * H + h) * LPT + c] = Tr::pack(acc);
+        for (int j = 0; j < G; ++j) {
+            if (j >= members) break;
+            const int64_t slot = ((int64_t)(s + j) * H + h) * parts_stride + part;
+            float *dst = P.ws_acc + slot * D + c * EPL;
+#pragma unroll
+            for (int e = 0; e < EPL; e += 4)
+                *reinterpret_cast<float4 *>(dst + e) =
+                    make_float4(acc[j][e], acc[j][e + 1], acc[j][e + 2], acc[j][e + 3]);
+            if (c == 0) *reinterpret_cast<float2 *>(P.ws_ml + slot * 2) = make_float2(m[j], l[j]);
+        }
     }
 }
 
-// Merge of the split-context partials: out = sum_p 2^(m_p-M) a_p / sum_p 2^(m_p-M) l_p
-// with a_p the unnormalised partial sums.  One wavefront per (sequence, head);
-// lane c handles the same 16-byte output fragment as in the decode kernel.
-template <int DT, int D>
-__global__ __launch_bounds__(kWave) void pa_reduce_kernel(
-    void *__restrict__ out, const int32_t *__restrict__ context_lens, int32_t H,
-    int32_t partition_size, int32_t max_parts, const float *__restrict__ ws_acc,
-    const float *__restrict__ ws_ml)
+// Merge of partials: out = sum_p 2^(m_p-M) a_p / sum_p 2^(m_p-M) l_p with a_p the
+// unnormalised partial sums.  One wavefront per (sequence, head); lane c
+// handles the same 16-byte output fragment as in the decode kernel.  With
+// fixed partitions the first ceil(n/PS) partials exist; on the shared-prefix
+// path partial 0 (prefix) exists when range_begin[s] > 0 and partial 1
+// (suffix) when range_begin[s] < n.
+template <int DT, int D, bool SHARED>
+__global__ __launch_bounds__(kWave) void pa_reduce_kernel(const DecodeParams P)
 {
     using Tr = Traits<DT>;
     constexpr int EPL = Tr::EPL;
     constexpr int LPT = D * Tr::E / 16;
     const int c = threadIdx.x;
     if (c >= LPT) return;
+    const int H = P.H;
     const int h = blockIdx.x % H;
     const int s = blockIdx.x / H;
-    const int n = context_lens[s];
-    int parts = (n + partition_size - 1) / partition_size;
-    if (parts > max_parts) parts = max_parts;
-    const int64_t base = ((int64_t)s * H + h) * max_parts;
+    const int n = P.context_lens[s];
+    int first = 0, last, stride;
+    if (SHARED) {
+        const int rb = P.ginfo[ginfo_range_begin(P.S, s)];
+        stride = 2;
+        first = rb > 0 ? 0 : 1;
+        last = n > rb ? 2 : 1;
+    } else {
+        stride = P.max_parts;
+        last = (n + P.partition_size - 1) / P.partition_size;
+        if (last > stride) last = stride;
+    }
+    const int64_t base = ((int64_t)s * H + h) * stride;
     float acc[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
-    if (parts > 0) {
+    if (n > 0 && first < last) {
         float M = kNegBig;
-        for (int p = 0; p < parts; ++p) M = fmaxf(M, ws_ml[(base + p) * 2]);
+        for (int p = first; p < last; ++p) M = fmaxf(M, P.ws_ml[(base + p) * 2]);
         float l = 0.f;
-        for (int p = 0; p < parts; ++p) {
-            const float2 ml = *reinterpret_cast<const float2 *>(ws_ml + (base + p) * 2);
+        for (int p = first; p < last; ++p) {
+            const float2 ml = *reinterpret_cast<const float2 *>(P.ws_ml + (base + p) * 2);
             const float f = __builtin_amdgcn_exp2f(ml.x - M);
             l = __builtin_fmaf(ml.y, f, l);
-            const float *src = ws_acc + (base + p) * D + c * EPL;
+            const float *src = P.ws_acc + (base + p) * D + c * EPL;
 #pragma unroll
             for (int e = 0; e < EPL; e += 4) {
                 const float4 a = *reinterpret_cast<const float4 *>(src + e);
@@ -430,7 +563,91 @@ __global__ __launch_bounds__(kWave) void pa_reduce_kernel(
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[e] *= inv;
     }
-    reinterpret_cast<uint4 *>(out)[((int64_t)s * H + h) * LPT + c] = Tr::pack(acc);
+    reinterpret_cast<uint4 *>(P.out)[((int64_t)s * H + h) * LPT + c] = Tr::pack(acc);
+}
+
+// Group discovery for the shared-prefix path.  Consecutive sequences whose
+// block tables start with the same physical blocks form a group (that is how
+// forked sequences sit in a batch: samples of one prompt, beams of one
+// search).  Only blocks that are full for both neighbours count, so every
+// token of a shared prefix is valid for every member.  A sequence joins the
+// current group while the group has room and the common prefix would keep at
+// least three quarters of its length; otherwise it opens a new group.
+// One workgroup; the scan over sequences is sequential and tiny.
+constexpr int kGroupMax = 4;
+constexpr int kGroupScanLds = 2048;   // sequences whose scan state fits in LDS
+__global__ __launch_bounds__(256) void find_groups_kernel(const int32_t *__restrict__ block_tables,
+                                                           int32_t max_blocks,
+                                                           const int32_t *__restrict__ context_lens,
+                                                           int32_t S, int32_t block_size,
+                                                           int32_t *__restrict__ ginfo)
+{
+    // The scan state lives in LDS when it fits (the sequential part then costs a
+    // few cycles per sequence); larger batches scan in the global table itself.
+    __shared__ int32_t lds[5 * kGroupScanLds];
+    const bool in_lds = S <= kGroupScanLds;
+    int32_t *range_begin = in_lds ? lds : ginfo + ginfo_range_begin(S, 0);
+    int32_t *g_start = in_lds ? lds + S : ginfo + ginfo_group_start(S, 0);
+    int32_t *g_size = in_lds ? lds + 2 * S : ginfo + ginfo_group_size(S, 0);
+    int32_t *g_prefix = in_lds ? lds + 3 * S : ginfo + ginfo_group_prefix(S, 0);
+    int32_t *adj = in_lds ? lds + 4 * S : ginfo + ginfo_adj(S, 0);
+
+    for (int s = threadIdx.x; s < S; s += 256) {
+        int a = 0;
+        if (s > 0) {
+            const int n0 = context_lens[s - 1], n1 = context_lens[s];
+            const int lim = (n0 < n1 ? n0 : n1) / block_size;
+            const int32_t *t0 = block_tables + (int64_t)(s - 1) * max_blocks;
+            const int32_t *t1 = block_tables + (int64_t)s * max_blocks;
+            while (a < lim && t0[a] == t1[a]) ++a;
+        }
+        adj[s] = a;
+    }
+    __syncthreads();
+    __shared__ int32_t num_groups;
+    if (threadIdx.x == 0) {
+        int ng = 0, start = 0, size = 0, prefix = 0;
+        auto close = [&]() {
+            const int tokens = size > 1 ? prefix * block_size : 0;
+            g_start[ng] = start;
+            g_size[ng] = size;
+            g_prefix[ng] = tokens;
+            for (int j = 0; j < size; ++j) range_begin[start + j] = tokens;
+            ++ng;
+        };
+        for (int s = 0; s < S; ++s) {
+            const int a = adj[s];
+            bool join = false;
+            if (size > 0 && size < kGroupMax && a > 0) {
+                const int np = size == 1 ? a : (a < prefix ? a : prefix);
+                join = size == 1 || 4 * np >= 3 * prefix;
+                if (join) prefix = np;
+            }
+            if (join) {
+                ++size;
+            } else {
+                if (size > 0) close();
+                start = s;
+                size = 1;
+                prefix = 0;
+            }
+        }
+        if (size > 0) close();
+        num_groups = ng;
+        ginfo[0] = ng;
+    }
+    __syncthreads();
+    if (in_lds) {
+        const int ng = num_groups;
+        for (int i = threadIdx.x; i < S; i += 256) {
+            ginfo[ginfo_range_begin(S, i)] = range_begin[i];
+            if (i < ng) {
+                ginfo[ginfo_group_start(S, i)] = g_start[i];
+                ginfo[ginfo_group_size(S, i)] = g_size[i];
+                ginfo[ginfo_group_prefix(S, i)] = g_prefix[i];
+            }
+        }
+    }
 }
 
 // ---- reshape_and_cache -------------------------------------------------------
@@ -456,7 +673,7 @@ __global__ __launch_bounds__(256) void reshape_and_cache_kernel(
     const int64_t dst = ((pb * H + h) * block_size + off) * frags_per_row + cfrag;
     const uint4 *src = blockIdx.y ? v : k;
     uint4 *cache = blockIdx.y ? v_cache : k_cache;
-    cache[dst] = src[idx];
+    store_frag_stream(cache + dst, load_frag_stream(src + idx));
 }
 
 // ---- copy_blocks -------------------------------------------------------------
@@ -478,16 +695,16 @@ __global__ __launch_bounds__(256) void copy_blocks_kernel(CachePtrs caches,
     const uint4 *sp = cache + src * frags_per_block;
     uint4 *dp = cache + dst * frags_per_block;
     const int64_t base = (int64_t)blockIdx.x * (256 * UNROLL) + threadIdx.x;
-    uint4 tmp[UNROLL];
+    u32x4_t tmp[UNROLL];
 #pragma unroll
     for (int i = 0; i < UNROLL; ++i) {
         const int64_t f = base + i * 256;
-        if (f < frags_per_block) tmp[i] = sp[f];
+        if (f < frags_per_block) tmp[i] = load_frag_stream(sp + f);
     }
 #pragma unroll
     for (int i = 0; i < UNROLL; ++i) {
         const int64_t f = base + i * 256;
-        if (f < frags_per_block) dp[f] = tmp[i];
+        if (f < frags_per_block) store_frag_stream(dp + f, tmp[i]);
     }
 }
 
@@ -537,72 +754,81 @@ bool shape_supported(pa_dtype dt, int D, int B)
 }
 
 struct DecodeArgs {
-    void *out;
-    const void *q;
-    const char *k_cache, *v_cache;
-    const int32_t *block_tables;
-    int32_t max_blocks;
-    const int32_t *context_lens;
-    int32_t S, H;
-    float scale_log2;
-    int32_t partition_size, max_parts;
+    DecodeParams p;
     int32_t waves;   // wavefronts per workgroup
-    float *ws_acc, *ws_ml;
     hipStream_t stream;
 };
 
-template <int DT, int D, int B, int W, bool PART>
-void launch_decode(const DecodeArgs &a)
+template <int DT, int D, int B, int W, int MODE, int G = 1>
+void launch_decode_kernel(const DecodeArgs &a, unsigned items)
 {
-    const unsigned grid = (unsigned)((int64_t)a.S * a.H * (PART ? a.max_parts : 1));
-    hipLaunchKernelGGL((pa_decode_kernel<DT, D, B, W, kChunksPerTrip, PART>), dim3(grid), dim3(W * kWave), 0,
-                       a.stream, a.out, a.q, a.k_cache, a.v_cache, a.block_tables, a.max_blocks,
-                       a.context_lens, a.H, a.scale_log2, a.partition_size, a.max_parts, a.ws_acc, a.ws_ml);
-    if (PART)
-        hipLaunchKernelGGL((pa_reduce_kernel<DT, D>), dim3((unsigned)(a.S * a.H)), dim3(kWave), 0,
-                           a.stream, a.out, a.context_lens, a.H, a.partition_size, a.max_parts,
-                           a.ws_acc, a.ws_ml);
+    hipLaunchKernelGGL((pa_decode_kernel<DT, D, B, W, (G > 1 ? 1 : kChunksPerTrip), MODE, G>),
+                       dim3(items * (unsigned)a.p.H),
+                       dim3(W * kWave), 0, a.stream, a.p);
 }
 
 template <int DT, int D, int B>
-void dispatch_mode(const DecodeArgs &a)
+void dispatch_mode(const DecodeArgs &a, int mode)
 {
-    if (a.partition_size > 0) {
+    const unsigned S = (unsigned)a.p.S;
+    const unsigned rows = S * (unsigned)a.p.H;
+    if (mode == MODE_PART) {
         if (a.waves >= 8)
-            launch_decode<DT, D, B, 8, true>(a);
+            launch_decode_kernel<DT, D, B, 8, MODE_PART>(a, S * (unsigned)a.p.max_parts);
         else
-            launch_decode<DT, D, B, 4, true>(a);
+            launch_decode_kernel<DT, D, B, 4, MODE_PART>(a, S * (unsigned)a.p.max_parts);
+        hipLaunchKernelGGL((pa_reduce_kernel<DT, D, false>), dim3(rows), dim3(kWave), 0, a.stream, a.p);
+    } else if (mode == MODE_PREFIX) {
+        // shared-prefix path: group table, prefixes once per group, private suffixes, merge
+        hipLaunchKernelGGL(find_groups_kernel, dim3(1), dim3(256), 0, a.stream, a.p.block_tables,
+                           a.p.max_blocks, a.p.context_lens, a.p.S, B, const_cast<int32_t *>(a.p.ginfo));
+#ifdef PA_TUNE_PREFIX_W
+        launch_decode_kernel<DT, D, B, PA_TUNE_PREFIX_W, MODE_PREFIX, kGroupMax>(a, S);
+#else
+        launch_decode_kernel<DT, D, B, 8, MODE_PREFIX, kGroupMax>(a, S);
+#endif
+        if (a.waves >= 16)
+            launch_decode_kernel<DT, D, B, 16, MODE_SUFFIX>(a, S);
+        else if (a.waves >= 8)
+            launch_decode_kernel<DT, D, B, 8, MODE_SUFFIX>(a, S);
+        else
+            launch_decode_kernel<DT, D, B, 4, MODE_SUFFIX>(a, S);
+        hipLaunchKernelGGL((pa_reduce_kernel<DT, D, true>), dim3(rows), dim3(kWave), 0, a.stream, a.p);
     } else {
         switch (a.waves) {
-        case 2: launch_decode<DT, D, B, 2, false>(a); break;
-        case 4: launch_decode<DT, D, B, 4, false>(a); break;
-        case 8: launch_decode<DT, D, B, 8, false>(a); break;
-        default: launch_decode<DT, D, B, 16, false>(a); break;
+        case 2: launch_decode_kernel<DT, D, B, 2, MODE_SINGLE>(a, S); break;
+        case 4: launch_decode_kernel<DT, D, B, 4, MODE_SINGLE>(a, S); break;
+        case 8: launch_decode_kernel<DT, D, B, 8, MODE_SINGLE>(a, S); break;
+#ifdef PA_TUNE_W
+        default: launch_decode_kernel<DT, D, B, PA_TUNE_W, MODE_SINGLE>(a, S); break;
+#else
+        default: launch_decode_kernel<DT, D, B, 16, MODE_SINGLE>(a, S); break;
+#endif
         }
     }
 }
 
 template <int DT, int D>
-bool dispatch_block(const DecodeArgs &a, int B)
+bool dispatch_block(const DecodeArgs &a, int B, int mode)
 {
     switch (B) {
-    case 8: dispatch_mode<DT, D, 8>(a); return true;
-    case 16: dispatch_mode<DT, D, 16>(a); return true;
-    case 32: dispatch_mode<DT, D, 32>(a); return true;
-    case 64: dispatch_mode<DT, D, 64>(a); return true;
-    case 128: dispatch_mode<DT, D, 128>(a); return true;
+    case 8: dispatch_mode<DT, D, 8>(a, mode); return true;
+    case 16: dispatch_mode<DT, D, 16>(a, mode); return true;
+    case 32: dispatch_mode<DT, D, 32>(a, mode); return true;
+    case 64: dispatch_mode<DT, D, 64>(a, mode); return true;
+    case 128: dispatch_mode<DT, D, 128>(a, mode); return true;
     }
     return false;
 }
 
-bool dispatch_decode(const DecodeArgs &a, pa_dtype dt, int D, int B)
+bool dispatch_decode(const DecodeArgs &a, pa_dtype dt, int D, int B, int mode)
 {
-    if (dt == PA_F32 && D == 64) return dispatch_block<PA_F32, 64>(a, B);
-    if (dt == PA_F32 && D == 128) return dispatch_block<PA_F32, 128>(a, B);
-    if (dt == PA_F16 && D == 64) return dispatch_block<PA_F16, 64>(a, B);
-    if (dt == PA_F16 && D == 128) return dispatch_block<PA_F16, 128>(a, B);
-    if (dt == PA_BF16 && D == 64) return dispatch_block<PA_BF16, 64>(a, B);
-    if (dt == PA_BF16 && D == 128) return dispatch_block<PA_BF16, 128>(a, B);
+    if (dt == PA_F32 && D == 64) return dispatch_block<PA_F32, 64>(a, B, mode);
+    if (dt == PA_F32 && D == 128) return dispatch_block<PA_F32, 128>(a, B, mode);
+    if (dt == PA_F16 && D == 64) return dispatch_block<PA_F16, 64>(a, B, mode);
+    if (dt == PA_F16 && D == 128) return dispatch_block<PA_F16, 128>(a, B, mode);
+    if (dt == PA_BF16 && D == 64) return dispatch_block<PA_BF16, 64>(a, B, mode);
+    if (dt == PA_BF16 && D == 128) return dispatch_block<PA_BF16, 128>(a, B, mode);
     return false;
 }
 
@@ -652,6 +878,23 @@ int auto_partition(int S, int H, int max_context_len)
     int64_t ps = (max_context_len + want_parts - 1) / want_parts;
     ps = ((ps + 255) / 256) * 256;   // a multiple of every supported block size
     return ps >= max_context_len ? 0 : (int)ps;
+}
+
+void fill_common(DecodeArgs &a, void *out, const void *q, const void *k_cache, const void *v_cache,
+                 const int32_t *block_tables, int32_t max_blocks, const int32_t *context_lens, int32_t S,
+                 int32_t H, float scale, void *stream)
+{
+    a.p.out = out;
+    a.p.q = q;
+    a.p.k_cache = static_cast<const char *>(k_cache);
+    a.p.v_cache = static_cast<const char *>(v_cache);
+    a.p.block_tables = block_tables;
+    a.p.max_blocks = max_blocks;
+    a.p.context_lens = context_lens;
+    a.p.S = S;
+    a.p.H = H;
+    a.p.scale_log2 = scale * kLog2e;
+    a.stream = static_cast<hipStream_t>(stream);
 }
 
 } // namespace
@@ -710,32 +953,65 @@ pa_status pa_decode(void *out, const void *q, const void *k_cache, const void *v
 
     DecodeArgs a;
     memset(&a, 0, sizeof(a));
-    a.out = out;
-    a.q = q;
-    a.k_cache = static_cast<const char *>(k_cache);
-    a.v_cache = static_cast<const char *>(v_cache);
-    a.block_tables = block_tables;
-    a.max_blocks = max_blocks_per_seq;
-    a.context_lens = context_lens;
-    a.S = num_seqs;
-    a.H = num_heads;
-    a.scale_log2 = scale * kLog2e;
-    a.partition_size = partition_size;
-    a.max_parts = 1;
+    fill_common(a, out, q, k_cache, v_cache, block_tables, max_blocks_per_seq, context_lens, num_seqs,
+                num_heads, scale, stream);
+    a.p.partition_size = partition_size;
+    a.p.max_parts = 1;
     a.waves = waves_for(partition_size > 0 ? partition_size : max_context_len,
                         chunk_tokens(dtype, head_dim, block_size));
-    a.stream = static_cast<hipStream_t>(stream);
     if (partition_size > 0) {
-        a.max_parts = (max_context_len + partition_size - 1) / partition_size;
+        a.p.max_parts = (max_context_len + partition_size - 1) / partition_size;
         const size_t need = pa_decode_workspace_bytes(num_seqs, num_heads, head_dim, block_size,
                                                       max_context_len, partition_size);
         if (!workspace || workspace_bytes < need) return PA_ERR_WORKSPACE;
         if (!aligned16(workspace)) return PA_ERR_ALIGN;
-        if ((int64_t)num_seqs * num_heads * a.max_parts > 0x7fffffff) return PA_ERR_SHAPE;
-        a.ws_acc = static_cast<float *>(workspace);
-        a.ws_ml = a.ws_acc + (size_t)num_seqs * num_heads * a.max_parts * head_dim;
+        if ((int64_t)num_seqs * num_heads * a.p.max_parts > 0x7fffffff) return PA_ERR_SHAPE;
+        a.p.ws_acc = static_cast<float *>(workspace);
+        a.p.ws_ml = a.p.ws_acc + (size_t)num_seqs * num_heads * a.p.max_parts * head_dim;
     }
-    if (!dispatch_decode(a, dtype, head_dim, block_size)) return PA_ERR_UNSUPPORTED;
+    if (!dispatch_decode(a, dtype, head_dim, block_size, partition_size > 0 ? MODE_PART : MODE_SINGLE))
+        return PA_ERR_UNSUPPORTED;
+    return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
+}
+
+size_t pa_decode_shared_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t head_dim)
+{
+    if (num_seqs <= 0 || num_heads <= 0 || head_dim <= 0) return 0;
+    const size_t partials = (size_t)num_seqs * num_heads * 2 * ((size_t)head_dim + 2) * sizeof(float);
+    return partials + ((ginfo_words(num_seqs) * sizeof(int32_t) + 15) & ~(size_t)15);
+}
+
+pa_status pa_decode_shared(void *out, const void *q, const void *k_cache, const void *v_cache,
+                           const int32_t *block_tables, int32_t max_blocks_per_seq,
+                           const int32_t *context_lens, int32_t num_seqs, int32_t num_heads,
+                           int32_t head_dim, int32_t block_size, int64_t num_blocks, pa_dtype dtype,
+                           float scale, int32_t max_context_len, void *workspace,
+                           size_t workspace_bytes, void *stream)
+{
+    if (num_seqs < 0 || num_heads <= 0 || head_dim <= 0 || block_size <= 0 || num_blocks <= 0 ||
+        max_blocks_per_seq <= 0 || max_context_len < 0)
+        return PA_ERR_SHAPE;
+    if (!shape_supported(dtype, head_dim, block_size)) return PA_ERR_UNSUPPORTED;
+    if ((int64_t)max_context_len > (int64_t)max_blocks_per_seq * block_size) return PA_ERR_SHAPE;
+    if (num_seqs == 0) return PA_OK;
+    if (!out || !q || !k_cache || !v_cache || !block_tables || !context_lens) return PA_ERR_NULL;
+    if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return PA_ERR_ALIGN;
+    if ((int64_t)num_seqs * num_heads > (int64_t)0x7fffffff / 64) return PA_ERR_SHAPE;
+    const size_t need = pa_decode_shared_workspace_bytes(num_seqs, num_heads, head_dim);
+    if (!workspace || workspace_bytes < need) return PA_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return PA_ERR_ALIGN;
+
+    DecodeArgs a;
+    memset(&a, 0, sizeof(a));
+    fill_common(a, out, q, k_cache, v_cache, block_tables, max_blocks_per_seq, context_lens, num_seqs,
+                num_heads, scale, stream);
+    a.p.max_parts = 2;
+    a.waves = waves_for(max_context_len, chunk_tokens(dtype, head_dim, block_size));
+    const size_t rows2 = (size_t)num_seqs * num_heads * 2;
+    a.p.ws_acc = static_cast<float *>(workspace);
+    a.p.ws_ml = a.p.ws_acc + rows2 * head_dim;
+    a.p.ginfo = reinterpret_cast<const int32_t *>(a.p.ws_ml + rows2 * 2);
+    if (!dispatch_decode(a, dtype, head_dim, block_size, MODE_PREFIX)) return PA_ERR_UNSUPPORTED;
     return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
 }
 

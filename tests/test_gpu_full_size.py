@@ -13,8 +13,8 @@ from harness import workloads as W
 
 pytestmark = pytest.mark.gpu
 
-from gpu_util import (TOL, DeviceWorkload, gpu_cache_ops, gpu_decode, oracle_cache_ops,  # noqa: E402
-                      out_to_f64, same_bits, to_dev, to_np)
+from gpu_util import (TOL, DeviceWorkload, gpu_cache_ops, gpu_decode, gpu_decode_shared,  # noqa: E402
+                      oracle_cache_ops, out_to_f64, same_bits, to_dev, to_np)
 
 
 @pytest.fixture(scope="module")
@@ -36,10 +36,10 @@ def full_check(pa, w, partitions):
     ref = oracle.decode(v.q, kc, vc, w.block_tables, w.context_lens, w.scale, w.dtype)
     errs = {}
     for ps in partitions:
-        out = out_to_f64(gpu_decode(pa, dw, ps), w.dtype)
+        out = out_to_f64(gpu_decode_shared(pa, dw) if ps == "shared" else gpu_decode(pa, dw, ps), w.dtype)
         assert np.isfinite(out).all()
         errs[ps] = float(np.abs(out - ref).max())
-        assert errs[ps] <= TOL[w.dtype], "%s ps=%d: max abs err %g" % (w.name, ps, errs[ps])
+        assert errs[ps] <= TOL[w.dtype], "%s ps=%s: max abs err %g" % (w.name, ps, errs[ps])
     print(w.name, errs)
     del dw
     torch.cuda.empty_cache()
@@ -47,14 +47,14 @@ def full_check(pa, w, partitions):
 
 @pytest.mark.timeout(300)
 def test_config2_full(pa):
-    full_check(pa, W.config2(), (pa.PA_PARTITION_AUTO, 0, 512))
+    full_check(pa, W.config2(), (pa.PA_PARTITION_AUTO, 0, 512, "shared"))
 
 
 @pytest.mark.timeout(300)
 def test_config3_full(pa):
     w = W.config3()
     assert w.num_seqs == 256 and len(w.copy_pairs) > 100 and len(w.write_slots) > 30000
-    full_check(pa, w, (pa.PA_PARTITION_AUTO, 256))
+    full_check(pa, w, (pa.PA_PARTITION_AUTO, 256, "shared"))
 
 
 @pytest.mark.timeout(300)

@@ -19,8 +19,11 @@ def pa():
     return pa
 
 
-from gpu_util import (TOL, DeviceWorkload, gpu_cache_ops, gpu_decode, oracle_cache_ops,  # noqa: E402
-                      out_to_f64, same_bits, to_dev, to_np)
+from gpu_util import (TOL, DeviceWorkload, gpu_cache_ops, gpu_decode, gpu_decode_shared,  # noqa: E402
+                      oracle_cache_ops, out_to_f64, same_bits, to_dev, to_np)
+
+
+SHARED = "shared"     # pseudo partition value: run pa_decode_shared
 
 
 def run_and_compare(pa, w, partitions=(0,), q_mult=1.0, seed=None, rows=None):
@@ -36,12 +39,12 @@ def run_and_compare(pa, w, partitions=(0,), q_mult=1.0, seed=None, rows=None):
     ref = oracle.decode(v.q, kc, vc, w.block_tables, w.context_lens, w.scale, w.dtype, rows=rows)
     errs = {}
     for ps in partitions:
-        out = out_to_f64(gpu_decode(pa, dw, ps), w.dtype)
+        out = out_to_f64(gpu_decode_shared(pa, dw) if ps == SHARED else gpu_decode(pa, dw, ps), w.dtype)
         if rows is not None:
             out = out[rows[:, 0], rows[:, 1]]
-        assert np.isfinite(out).all(), "%s ps=%d: non-finite output" % (w.name, ps)
+        assert np.isfinite(out).all(), "%s ps=%s: non-finite output" % (w.name, ps)
         errs[ps] = float(np.abs(out - ref).max())
-        assert errs[ps] <= TOL[w.dtype], "%s ps=%d: max abs err %g" % (w.name, ps, errs[ps])
+        assert errs[ps] <= TOL[w.dtype], "%s ps=%s: max abs err %g" % (w.name, ps, errs[ps])
     return errs
 
 
@@ -93,6 +96,66 @@ def test_every_workgroup_width(pa, max_len):
     for dtype in ("f16", "bf16"):
         w = W.independent_sequences("widths", dtype, 3, 128, 16, lens, seed=max_len)
         print(dtype, run_and_compare(pa, w, partitions=(0, 64, 512, 1024)))
+
+
+# ---------------------------------------------------------------------------
+# shared-prefix decode: same oracle, same tolerance
+# ---------------------------------------------------------------------------
+def test_shared_decode_parallel_sampling(pa):
+    w = W.config3(num_groups=7, H=4, prompt_median=80, prompt_cap=300, max_out=90)
+    print(run_and_compare(pa, w, partitions=(SHARED, 0)))
+
+
+def test_shared_decode_beam_groups_of_six(pa):
+    # groups larger than the kernel's query slots are split; beams share 55% of their blocks
+    w = W.config5(num_seqs=20, H=3, min_len=100, max_len=900)
+    print(run_and_compare(pa, w, partitions=(SHARED, 0)))
+
+
+def test_shared_decode_without_sharing(pa):
+    # nothing in common: every sequence is a group of one and only the suffix path runs
+    for dtype, D in (("f16", 128), ("bf16", 128), ("f32", 64)):
+        rng = np.random.default_rng(31)
+        lens = np.concatenate([rng.integers(1, 500, size=9), [0, 1, 16]])
+        w = W.independent_sequences("private", dtype, 3, D, 16, lens, seed=32)
+        print(dtype, run_and_compare(pa, w, partitions=(SHARED,)))
+
+
+def test_shared_decode_fully_shared_and_mixed(pa):
+    # forks that have not diverged (every block shared, the partial last one included), a group
+    # whose members share different numbers of blocks, a loner in between, and a group of 5
+    from harness.blocks import BlockManager
+    rng = np.random.default_rng(33)
+    B, NB, H, D = 16, 400, 2, 128
+    mgr = BlockManager(NB, B, order=rng.permutation(NB))
+    seqs = []
+    a = mgr.allocate(70)
+    seqs += [a, mgr.fork(a), mgr.fork(a)]                     # identical: 4 full blocks + 6 tokens
+    seqs.append(mgr.allocate(33))                             # loner
+    b = mgr.allocate(200)
+    kids = [mgr.fork(b) for _ in range(4)]
+    grow = [0, 5, 40, 90, 17]
+    for sq, gsteps in zip([b] + kids, grow):
+        for _ in range(gsteps):
+            mgr.append(sq)
+    seqs += [b] + kids                                        # group of 5 -> 4 + 1
+    c = mgr.allocate(16)
+    seqs += [c, mgr.fork(c)]                                  # exactly one shared full block, nothing else
+    mgr.take_copies()
+    for dtype in ("f16", "bf16"):
+        filled = np.zeros((NB, B), dtype=bool)
+        for sq in seqs:
+            for j, pb in enumerate(sq.blocks):
+                filled[pb, : min(B, sq.length - j * B)] = True
+        mb = max(len(sq.blocks) for sq in seqs) + 1
+        bt = np.full((len(seqs), mb), -1, dtype=np.int32)
+        for i, sq in enumerate(seqs):
+            bt[i, : len(sq.blocks)] = sq.blocks
+        w = W.Workload("mixed", dtype, H, D, B, NB, np.float32(1 / np.sqrt(D)), bt,
+                       np.array([sq.length for sq in seqs], dtype=np.int32), filled,
+                       np.zeros((0, 2), dtype=np.int64), np.zeros(0, dtype=np.int64),
+                       np.zeros(len(seqs), dtype=np.int64), seed=34)
+        print(dtype, run_and_compare(pa, w, partitions=(SHARED, 0)))
 
 
 def test_edge_context_lengths(pa):
