@@ -43,6 +43,10 @@ def parse():
                     help="also run one pa_copy_blocks of known size (a plain copy kernel that "
                          "hardware-counter runs use to scale FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--block-size-sweep", action="store_true",
+                    help="instead of the step benchmark: pa_decode at the OPT-13B shape for B = 8..128")
+    ap.add_argument("--cache-ops", action="store_true",
+                    help="instead of the step benchmark: pa_reshape_and_cache and pa_copy_blocks at several sizes")
     return ap.parse_args()
 
 
@@ -61,6 +65,84 @@ def profiled_traffic(workload_name):
     except (OSError, KeyError, ValueError):
         pass
     return None
+
+
+def _time_us(fn, iters, torch):
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters * 1e3
+
+
+def block_size_sweep(pa, W, np, torch, dev):
+    """The paper's block-size ablation axis (Sec. 7.2) as a kernel microbenchmark: same sequences,
+    same bytes, different B.  Caches are filled on the device (timing only)."""
+    rng = np.random.default_rng(2000)
+    lens = rng.integers(1, 2049, size=64)
+    rows = []
+    for B in (8, 16, 32, 64, 128):
+        w = W.independent_sequences("opt13b_B%d" % B, "f16", 40, 128, B, lens, 2001)
+        shape = (w.num_blocks, 40, B, 128)
+        kc = torch.randn(shape, dtype=torch.float16, device=dev)
+        vc = torch.randn(shape, dtype=torch.float16, device=dev)
+        q = torch.randn((64, 40, 128), dtype=torch.float16, device=dev)
+        out = torch.empty_like(q)
+        bt = torch.from_numpy(w.block_tables).to(dev)
+        cl = torch.from_numpy(w.context_lens).to(dev)
+        us = _time_us(lambda: pa.pa_decode(out, q, kc, vc, bt, cl, B, float(w.scale), w.max_context_len, 0, None),
+                      100, torch)
+        rows.append({"block_size": B, "us": us, "kv_GBps": w.kv_bytes_logical() / us / 1e3,
+                     "frac_of_peak": w.kv_bytes_logical() / us / 1e3 / HBM_PEAK_GBPS,
+                     "pool_blocks": w.num_blocks})
+        del kc, vc
+    print(json.dumps({"metric": "pa_decode_block_size_sweep", "workload": "OPT-13B shape, 64 seq, ctx U{1..2048}, fp16",
+                      "rows": rows}))
+
+
+def cache_ops(pa, np, torch, dev):
+    """pa_reshape_and_cache from decode-step to prefill-sized token counts, pa_copy_blocks from a few
+    pairs to thousands, at the OPT-13B layer shape; GB/s counts bytes read plus bytes written."""
+    H, D, B, NB = 40, 128, 16, 8192
+    kc = torch.zeros((NB, H, B, D), dtype=torch.float16, device=dev)
+    vc = torch.zeros_like(kc)
+    rng = np.random.default_rng(5)
+    res = {"reshape_and_cache": [], "copy_blocks": []}
+    for T in (64, 256, 1024, 4096, 16384, 65536):
+        k = torch.randn((T, H, D), dtype=torch.float16, device=dev)
+        v = torch.randn((T, H, D), dtype=torch.float16, device=dev)
+        slots = torch.from_numpy(rng.permutation(NB * B)[:T].astype(np.int64)).to(dev)
+        us = _time_us(lambda: pa.pa_reshape_and_cache(k, v, kc, vc, slots), 50, torch)
+        moved = 2 * 2 * T * H * D * 2
+        res["reshape_and_cache"].append({"tokens": T, "us": us, "GBps": moved / us / 1e3})
+    for N in (4, 41, 183, 1024, 4096):
+        perm = rng.permutation(NB)
+        pairs = torch.from_numpy(np.stack([perm[:N], perm[N:2 * N]], axis=1).astype(np.int64)).to(dev)
+        us = _time_us(lambda: pa.pa_copy_blocks([kc], [vc], pairs), 50, torch)
+        moved = 2 * 2 * N * H * B * D * 2
+        res["copy_blocks"].append({"pairs": N, "us": us, "GBps": moved / us / 1e3})
+    # swap to pinned host memory and back (one direction per call); GB/s counts bytes moved once
+    res["swap_blocks"] = []
+    NBH = 1024
+    hk = torch.empty((NBH, H, B, D), dtype=torch.float16, pin_memory=True)
+    hv = torch.empty((NBH, H, B, D), dtype=torch.float16, pin_memory=True)
+    for N in (16, 128, 1024):
+        gpu_ids, cpu_ids = rng.permutation(NB)[:N], rng.permutation(NBH)[:N]
+        out_pairs = torch.from_numpy(np.stack([gpu_ids, cpu_ids], axis=1).astype(np.int64)).to(dev)
+        in_pairs = torch.from_numpy(np.stack([cpu_ids, gpu_ids], axis=1).astype(np.int64)).to(dev)
+        moved = 2 * N * H * B * D * 2
+        us_out = _time_us(lambda: pa.pa_swap_blocks([kc], [vc], [hk], [hv], out_pairs), 10, torch)
+        us_in = _time_us(lambda: pa.pa_swap_blocks([hk], [hv], [kc], [vc], in_pairs), 10, torch)
+        res["swap_blocks"].append({"blocks": N, "out_us": us_out, "out_GBps": moved / us_out / 1e3,
+                                   "in_us": us_in, "in_GBps": moved / us_in / 1e3})
+    res["metric"] = "cache_ops_read_plus_write_GBps"
+    res["shape"] = "H=40, D=128, B=16, fp16, pool of 8192 blocks"
+    print(json.dumps(res))
 
 
 def main():
@@ -82,6 +164,11 @@ def main():
     pa.load_library()
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+
+    if args.block_size_sweep:
+        return block_size_sweep(pa, W, np, torch, dev)
+    if args.cache_ops:
+        return cache_ops(pa, np, torch, dev)
 
     make = {"cfg1": W.config1, "cfg2": W.config2, "cfg3": W.config3, "cfg4": W.config4,
             "cfg5": W.config5}[args.workload]

@@ -171,6 +171,30 @@ pa_status pa_copy_blocks(void *const *k_caches, void *const *v_caches, int32_t n
                          pa_dtype dtype, void *stream);
 
 /*
+ * pa_swap_blocks - block copies between two sets of caches in one launch:
+ * swapping evicted blocks out to CPU memory and back (Sec. 4.5, "Swapping":
+ * evicted blocks are copied to CPU RAM, managed by a CPU block allocator, and
+ * brought back when the sequence is rescheduled).  For every layer l and pair
+ * i: dst_k_caches[l][dst_i] = src_k_caches[l][src_i], and the same for v.
+ *
+ * Either side may be device memory or PINNED host memory that the device can
+ * address (hipHostMalloc / a torch tensor with pin_memory=True): the kernel
+ * reads and writes it directly, so one launch moves all blocks of all layers
+ * instead of one small transfer per block.  The caller synchronises `stream`
+ * before the CPU touches host-side blocks.
+ *
+ *   src_*_caches, dst_*_caches  HOST arrays of num_layers pointers to
+ *                       [src_num_blocks][H][B][D] / [dst_num_blocks][H][B][D] caches
+ *   src_dst_pairs       device [num_pairs][2] int64: (block id in src, block id in dst);
+ *                       destinations are distinct
+ */
+pa_status pa_swap_blocks(void *const *src_k_caches, void *const *src_v_caches,
+                         void *const *dst_k_caches, void *const *dst_v_caches, int32_t num_layers,
+                         const int64_t *src_dst_pairs, int32_t num_pairs, int32_t num_heads,
+                         int32_t head_dim, int32_t block_size, int64_t src_num_blocks,
+                         int64_t dst_num_blocks, pa_dtype dtype, void *stream);
+
+/*
  * pa_debug_validate - check the device index arrays of a decode step against
  * the undefined-behaviour list above.  Copies them to the host, synchronises
  * the stream, and returns PA_ERR_INVALID on the first violation.  Any of

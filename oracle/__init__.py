@@ -49,6 +49,8 @@ def _load():
         lib.pa_oracle_reshape_and_cache.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32]
         lib.pa_oracle_copy_blocks.restype = None
         lib.pa_oracle_copy_blocks.argtypes = [vp, vp, i32, vp, i32, i32, i32, i32, i32]
+        lib.pa_oracle_swap_blocks.restype = None
+        lib.pa_oracle_swap_blocks.argtypes = [vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i32]
         lib.pa_oracle_max_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -122,3 +124,23 @@ def copy_blocks(k_caches: Sequence[np.ndarray], v_caches: Sequence[np.ndarray],
     vp = (ctypes.c_void_p * L)(*[c.ctypes.data for c in v_caches])
     _load().pa_oracle_copy_blocks(kp, vp, L, _ptr(pairs), pairs.shape[0], H, D, B,
                                   DTYPE_CODE[dtype])
+
+
+def swap_blocks(src_k: Sequence[np.ndarray], src_v: Sequence[np.ndarray], dst_k: Sequence[np.ndarray],
+                dst_v: Sequence[np.ndarray], src_dst_pairs: np.ndarray, dtype: str) -> None:
+    """In place on the destination pools, for every layer: dst[dst_block] = src[src_block]."""
+    st = _NP_OF[dtype]
+    L = len(src_k)
+    assert L >= 1 and len(src_v) == L and len(dst_k) == L and len(dst_v) == L
+    pairs = _chk(np.asarray(src_dst_pairs), np.int64, "src_dst_pairs").reshape(-1, 2)
+    NBS, H, B, D = src_k[0].shape
+    NBD = dst_k[0].shape[0]
+    for c in list(src_k) + list(src_v):
+        _chk(c, st, "cache"); assert c.shape == (NBS, H, B, D)
+    for c in list(dst_k) + list(dst_v):
+        _chk(c, st, "cache"); assert c.shape == (NBD, H, B, D)
+    if pairs.size:
+        assert pairs.min() >= 0 and pairs[:, 0].max() < NBS and pairs[:, 1].max() < NBD
+    arr = lambda cs: (ctypes.c_void_p * L)(*[c.ctypes.data for c in cs])
+    _load().pa_oracle_swap_blocks(arr(src_k), arr(src_v), arr(dst_k), arr(dst_v), L, _ptr(pairs),
+                                  pairs.shape[0], H, D, B, DTYPE_CODE[dtype])

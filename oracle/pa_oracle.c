@@ -19,6 +19,7 @@
  *   - Sec. 4.3 / 5.1(1): new K/V vectors are stored at the slot their block
  *     table position names (slot = physical_block * B + offset).
  *   - Sec. 4.4 / 5.1(3): copy-on-write copies a whole physical block.
+ *   - Sec. 4.5 (swapping): whole blocks move between a GPU pool and a CPU pool.
  *
  * Cache layout (the paper leaves it open, Sec. 5.1(1)); element (block pb,
  * head h, offset off, dim d) of a cache array sits at index
@@ -265,6 +266,29 @@ void pa_oracle_copy_blocks(void *const *k_caches, void *const *v_caches, int32_t
                     (const char *)k_caches[l] + src * block_bytes, block_bytes);
             memmove((char *)v_caches[l] + dst * block_bytes,
                     (const char *)v_caches[l] + src * block_bytes, block_bytes);
+        }
+    }
+}
+
+/*
+ * Swapping (Sec. 4.5): evicted blocks are copied to another pool (CPU memory)
+ * and later copied back.  For each layer and each pair (src, dst) in order:
+ * the whole block src of the source pool is copied to block dst of the
+ * destination pool, for K and for V.
+ */
+void pa_oracle_swap_blocks(void *const *src_k, void *const *src_v, void *const *dst_k,
+                           void *const *dst_v, int32_t num_layers, const int64_t *src_dst_pairs,
+                           int32_t num_pairs, int32_t num_heads, int32_t head_dim,
+                           int32_t block_size, int32_t dtype)
+{
+    size_t block_bytes = (size_t)num_heads * block_size * head_dim * elem_bytes(dtype);
+    for (int l = 0; l < num_layers; ++l) {
+        for (int i = 0; i < num_pairs; ++i) {
+            int64_t src = src_dst_pairs[2 * i], dst = src_dst_pairs[2 * i + 1];
+            memcpy((char *)dst_k[l] + dst * block_bytes, (const char *)src_k[l] + src * block_bytes,
+                   block_bytes);
+            memcpy((char *)dst_v[l] + dst * block_bytes, (const char *)src_v[l] + src * block_bytes,
+                   block_bytes);
         }
     }
 }

@@ -18,7 +18,7 @@ from .build import LIB
 PA_F32, PA_F16, PA_BF16 = 0, 1, 2
 PA_PARTITION_AUTO = -1
 
-EXPORTS = ("pa_decode", "pa_decode_workspace_bytes", "pa_decode_shared", "pa_decode_shared_workspace_bytes", "pa_reshape_and_cache", "pa_copy_blocks",
+EXPORTS = ("pa_decode", "pa_decode_workspace_bytes", "pa_decode_shared", "pa_decode_shared_workspace_bytes", "pa_reshape_and_cache", "pa_copy_blocks", "pa_swap_blocks",
            "pa_debug_validate", "pa_stream_read", "pa_status_string", "pa_version")
 
 _DT = {torch.float32: PA_F32, torch.float16: PA_F16, torch.bfloat16: PA_BF16}
@@ -56,6 +56,8 @@ def load_library() -> ctypes.CDLL:
     lib.pa_reshape_and_cache.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, ctypes.c_int, vp]
     lib.pa_copy_blocks.restype = ctypes.c_int
     lib.pa_copy_blocks.argtypes = [vp, vp, i32, vp, i32, i32, i32, i32, i64, ctypes.c_int, vp]
+    lib.pa_swap_blocks.restype = ctypes.c_int
+    lib.pa_swap_blocks.argtypes = [vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i64, i64, ctypes.c_int, vp]
     lib.pa_debug_validate.restype = ctypes.c_int
     lib.pa_debug_validate.argtypes = [vp, i32, vp, i32, i32, vp, i32, vp, i32, i32, i64, vp]
     lib.pa_stream_read.restype = ctypes.c_int
@@ -173,6 +175,32 @@ def pa_copy_blocks(k_caches: Sequence[torch.Tensor], v_caches: Sequence[torch.Te
     n = src_dst_pairs.shape[0]
     _check(load_library().pa_copy_blocks(
         kp, vp, L, _dev(src_dst_pairs, "src_dst_pairs", torch.int64) if n else None, n, H, D, B, NB,
+        _DT[dtype], _stream()))
+
+
+def pa_swap_blocks(src_k: Sequence[torch.Tensor], src_v: Sequence[torch.Tensor],
+                   dst_k: Sequence[torch.Tensor], dst_v: Sequence[torch.Tensor],
+                   src_dst_pairs: torch.Tensor) -> None:
+    """For every layer: dst[dst_block] = src[src_block] per (src_block, dst_block) row of src_dst_pairs.
+    Caches on either side may be GPU tensors or pinned CPU tensors."""
+    L = len(src_k)
+    if L == 0 or len(src_v) != L or len(dst_k) != L or len(dst_v) != L:
+        raise ValueError("need the same number of layers on every side")
+    NBS, H, B, D = src_k[0].shape
+    NBD = dst_k[0].shape[0]
+    dtype = src_k[0].dtype
+    for c, nb in [(x, NBS) for x in list(src_k) + list(src_v)] + [(x, NBD) for x in list(dst_k) + list(dst_v)]:
+        if c.shape != (nb, H, B, D) or c.dtype != dtype or not c.is_contiguous():
+            raise ValueError("caches of one side must share shape and dtype and be contiguous")
+        if not (c.is_cuda or c.is_pinned()):
+            raise ValueError("a cache must live on the GPU or in pinned host memory")
+    if src_dst_pairs.dim() != 2 or src_dst_pairs.shape[1] != 2:
+        raise ValueError("src_dst_pairs must be [N][2]")
+    arr = lambda ts: (ctypes.c_void_p * L)(*[t.data_ptr() for t in ts])
+    n = src_dst_pairs.shape[0]
+    _check(load_library().pa_swap_blocks(
+        arr(src_k), arr(src_v), arr(dst_k), arr(dst_v), L,
+        _dev(src_dst_pairs, "src_dst_pairs", torch.int64) if n else None, n, H, D, B, NBS, NBD,
         _DT[dtype], _stream()))
 
 

@@ -275,6 +275,44 @@ def test_copy_blocks_many_layers_two_launches(pa):
         assert same_bits(dks[l], ks[l], "f16") and same_bits(dvs[l], vs[l], "f16")
 
 
+def test_swap_blocks_to_pinned_host_and_back(pa):
+    # Sec. 4.5: evicted blocks go to a CPU pool (pinned, device-addressable) and return to other blocks
+    rng = np.random.default_rng(24)
+    L, NBG, NBC, H, B, D = 3, 60, 40, 5, 16, 128
+    for dtype in ("f16", "bf16"):
+        gk = [W.to_storage(rng.standard_normal((NBG, H, B, D)).astype(np.float32), dtype) for _ in range(L)]
+        gv = [W.to_storage(rng.standard_normal((NBG, H, B, D)).astype(np.float32), dtype) for _ in range(L)]
+        ck = [W.to_storage(rng.standard_normal((NBC, H, B, D)).astype(np.float32), dtype) for _ in range(L)]
+        cv = [W.to_storage(rng.standard_normal((NBC, H, B, D)).astype(np.float32), dtype) for _ in range(L)]
+        tdt = torch.bfloat16 if dtype == "bf16" else torch.float16
+
+        def pinned(a):
+            t = torch.empty(a.shape, dtype=tdt, pin_memory=True)
+            src = torch.from_numpy(a)
+            t.copy_(src.view(torch.bfloat16) if dtype == "bf16" else src)
+            return t
+
+        dgk, dgv = [to_dev(x, dtype) for x in gk], [to_dev(x, dtype) for x in gv]
+        hck, hcv = [pinned(x) for x in ck], [pinned(x) for x in cv]
+        perm_g, perm_c = rng.permutation(NBG), rng.permutation(NBC)
+        out_pairs = np.stack([perm_g[:25], perm_c[:25]], axis=1).astype(np.int64)
+        pa.pa_swap_blocks(dgk, dgv, hck, hcv, to_dev(out_pairs))
+        torch.cuda.synchronize()
+        oracle.swap_blocks(gk, gv, ck, cv, out_pairs, dtype)
+        for l in range(L):
+            assert same_bits(hck[l], ck[l], dtype) and same_bits(hcv[l], cv[l], dtype)
+        # the freed GPU blocks get overwritten, then the swapped-out blocks come back into other blocks
+        for l in range(L):
+            dgk[l][to_dev(perm_g[:25])] = 0
+            gk[l][perm_g[:25]] = 0
+        in_pairs = np.stack([perm_c[:25], rng.permutation(NBG)[:25]], axis=1).astype(np.int64)
+        pa.pa_swap_blocks(hck, hcv, dgk, dgv, to_dev(in_pairs))
+        torch.cuda.synchronize()
+        oracle.swap_blocks(ck, cv, gk, gv, in_pairs, dtype)
+        for l in range(L):
+            assert same_bits(dgk[l], gk[l], dtype) and same_bits(dgv[l], gv[l], dtype)
+
+
 def test_debug_validate_flags_bad_indices(pa):
     w = W.config1()
     bt, cl = to_dev(w.block_tables), to_dev(w.context_lens)

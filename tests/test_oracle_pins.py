@@ -401,6 +401,33 @@ def test_copy_blocks_matches_numpy_and_example():
         assert np.array_equal(ks[l], wk[l])
 
 
+def test_swap_blocks_matches_numpy_round_trip():
+    # Sec. 4.5: blocks go out to a second pool and come back elsewhere; contents survive bit for bit
+    rng = np.random.default_rng(17)
+    L, NBG, NBC, H, B, D = 2, 12, 7, 2, 4, 8
+    gk = [W.to_storage(rng.standard_normal((NBG, H, B, D)).astype(np.float32), "f16") for _ in range(L)]
+    gv = [W.to_storage(rng.standard_normal((NBG, H, B, D)).astype(np.float32), "f16") for _ in range(L)]
+    ck = [np.zeros((NBC, H, B, D), dtype=np.float16) for _ in range(L)]
+    cv = [np.zeros((NBC, H, B, D), dtype=np.float16) for _ in range(L)]
+    keep_k, keep_v = [x.copy() for x in gk], [x.copy() for x in gv]
+    out_pairs = np.array([[3, 0], [11, 6], [5, 2]], dtype=np.int64)          # gpu block -> cpu block
+    oracle.swap_blocks(gk, gv, ck, cv, out_pairs, "f16")
+    for l in range(L):
+        want = np.zeros_like(ck[l])
+        want[out_pairs[:, 1]] = keep_k[l][out_pairs[:, 0]]
+        assert np.array_equal(ck[l], want)
+        assert np.array_equal(cv[l][6], keep_v[l][11]) and not np.array_equal(cv[l][6], ck[l][6])
+        assert np.array_equal(gk[l], keep_k[l])                                 # the source pool is untouched
+    for l in range(L):
+        gk[l][:] = 0
+        gv[l][:] = 0
+    in_pairs = np.array([[0, 9], [6, 1], [2, 4]], dtype=np.int64)             # cpu block -> new gpu block
+    oracle.swap_blocks(ck, cv, gk, gv, in_pairs, "f16")
+    for l in range(L):
+        assert np.array_equal(gk[l][9], keep_k[l][3]) and np.array_equal(gv[l][1], keep_v[l][11])
+        assert np.array_equal(gk[l][4], keep_k[l][5]) and not gk[l][0].any()
+
+
 def test_full_timeline_small_sharing_workload():
     # copy-on-write, writes, then decode on a shrunken parallel-sampling workload:
     # every slot decode reads must have been produced by the timeline (no NaN leaks)
