@@ -113,17 +113,18 @@ size_t pa_decode_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t he
  * blocks (Sec. 4.4: samples of one prompt and beams of one search map their
  * common logical blocks to the same physical blocks).  Same arguments, same
  * result as pa_decode; the difference is traffic.  The library compares the
- * block tables of consecutive sequences on the device, groups up to 4
- * neighbours whose tables start with the same full blocks, reads that common
- * prefix once per group while applying it to every member's query, reads
- * each sequence's remaining tokens separately, and merges the two partial
- * results per sequence with the log-sum-exp rule (the split-context merge).
- * Sequences that share nothing are handled as groups of one.
+ * block tables of consecutive sequences on the device, groups up to 8
+ * neighbours (4 for fp32 or head_dim 64) whose tables start with the same
+ * full blocks, reads that common prefix once per group while applying it to
+ * every member's query (on the matrix cores for 2-byte types at head_dim 128),
+ * reads each sequence's remaining tokens separately, and merges the two
+ * partial results per sequence with the log-sum-exp rule (the split-context
+ * merge).  Sequences that share nothing are handled as groups of one.
  *
  * Callers should place sequences that were forked from one another next to
  * each other in the batch; any order is correct, only adjacent sharing is
  * exploited.  `workspace` must hold pa_decode_shared_workspace_bytes(...)
- * bytes.  Four kernels are enqueued on `stream`.
+ * bytes.  Three or four kernels are enqueued on `stream`.
  */
 pa_status pa_decode_shared(void *out, const void *q, const void *k_cache, const void *v_cache,
                            const int32_t *block_tables, int32_t max_blocks_per_seq,

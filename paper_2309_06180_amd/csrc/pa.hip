@@ -27,6 +27,14 @@
 namespace {
 
 constexpr int kWave = 64;
+#ifndef PA_CHUNKS_PER_TRIP
+#define PA_CHUNKS_PER_TRIP 2
+#endif
+// chunks requested together per trip of the steady-state loop
+constexpr int kChunksPerTrip = PA_CHUNKS_PER_TRIP;
+constexpr int kChunksPerTripDevice = PA_CHUNKS_PER_TRIP;
+constexpr int kGroupMax = 4;       // query slots of the VALU shared-prefix kernel
+constexpr int kGroupMaxMfma = 8;   // query slots used of the 16 rows of the MFMA shared-prefix kernel
 constexpr float kLog2e = 1.4426950408889634f;
 // running-maximum start value: finite, so that (m - m) is 0 and never NaN
 constexpr float kNegBig = -3.0e38f;
@@ -231,19 +239,22 @@ struct DecodeParams {
     float *ws_acc, *ws_ml;
     int32_t max_blocks, S, H;
     int32_t partition_size, max_parts;
+    int32_t prefix_blocks;   // fused shared-prefix launch: workgroups [0, prefix_blocks) are prefix items
     float scale_log2;
 };
 
-// Layout of the group table: [0] = number of groups, then five arrays of S
-// entries: range_begin[s] (tokens of s covered by its group's shared prefix),
-// group_start[g], group_size[g], group_prefix_tokens[g], and adj[s] (leading
-// blocks that s has in common with s-1; scratch of the discovery kernel).
-__device__ __host__ __forceinline__ int ginfo_range_begin(int S, int s) { (void)S; return 4 + s; }
-__device__ __host__ __forceinline__ int ginfo_group_start(int S, int g) { return 4 + S + g; }
-__device__ __host__ __forceinline__ int ginfo_group_size(int S, int g) { return 4 + 2 * S + g; }
-__device__ __host__ __forceinline__ int ginfo_group_prefix(int S, int g) { return 4 + 3 * S + g; }
-__device__ __host__ __forceinline__ int ginfo_adj(int S, int s) { return 4 + 4 * S + s; }
-__device__ __host__ __forceinline__ size_t ginfo_words(int S) { return 4 + 5 * (size_t)S; }
+// Layout of the group table, three arrays of S entries: range_begin[s] (tokens
+// of s covered by its group's shared prefix), group_size[s] (members of the
+// group that starts at sequence s, 0 if none starts there) and
+// group_prefix_tokens[s] (tokens all members of that group have in common).
+__device__ __host__ __forceinline__ int ginfo_range_begin(int S, int s) { (void)S; return s; }
+__device__ __host__ __forceinline__ int ginfo_group_size(int S, int s) { return S + s; }
+__device__ __host__ __forceinline__ int ginfo_group_prefix(int S, int s) { return 2 * S + s; }
+__device__ __host__ __forceinline__ int ginfo_adj(int S, int s) { return 3 * S + s; }
+// compact list of the first sequences of groups with two or more members, and its length
+__device__ __host__ __forceinline__ int ginfo_shared_list(int S, int i) { return 4 * S + i; }
+__device__ __host__ __forceinline__ int ginfo_shared_count(int S) { return 5 * S; }
+__device__ __host__ __forceinline__ size_t ginfo_words(int S) { return 5 * (size_t)S + 4; }
 
 #ifdef PA_TUNE_OCC
 #define PA_OCC_ATTR __attribute__((amdgpu_waves_per_eu(PA_TUNE_OCC, PA_TUNE_OCC)))
@@ -254,8 +265,9 @@ __device__ __host__ __forceinline__ size_t ginfo_words(int S) { return 4 + 5 * (
 // of the launch by more than their overlap gains.
 #define PA_OCC_ATTR __attribute__((amdgpu_waves_per_eu(W == 16 ? 4 : 1, W == 16 ? 7 : 8)))
 #endif
+#define PA_OCC_ATTR_FUSED __attribute__((amdgpu_waves_per_eu(WS == 16 ? 4 : 1, WS == 16 ? 7 : 8)))
 template <int DT, int D, int B, int W, int U, int MODE, int G>
-__global__ __launch_bounds__(W *kWave) PA_OCC_ATTR void pa_decode_kernel(const DecodeParams P)
+__device__ __forceinline__ void decode_body(const DecodeParams &P, const int block_index)
 {
     using Tr = Traits<DT>;
     constexpr int E = Tr::E, EPL = Tr::EPL;
@@ -275,17 +287,17 @@ __global__ __launch_bounds__(W *kWave) PA_OCC_ATTR void pa_decode_kernel(const D
     const uint32_t lane16 = (uint32_t)lane * 16u;
     const int H = P.H;
 
-    int item = blockIdx.x;
+    int item = block_index;
     const int h = item % H;
     item /= H;
 
     // s: the sequence whose block table is walked; members: query slots in use
     int s, part = 0, parts_stride = 1, t_begin = 0, t_end, members = 1;
     if (MODE == MODE_PREFIX) {
-        if (item >= P.ginfo[0]) return;
-        s = P.ginfo[ginfo_group_start(P.S, item)];
-        members = P.ginfo[ginfo_group_size(P.S, item)];
-        t_end = P.ginfo[ginfo_group_prefix(P.S, item)];
+        if (item >= P.ginfo[ginfo_shared_count(P.S)]) return;
+        s = P.ginfo[ginfo_shared_list(P.S, item)];   // a group is named by its first sequence
+        members = P.ginfo[ginfo_group_size(P.S, s)];
+        t_end = P.ginfo[ginfo_group_prefix(P.S, s)];
         parts_stride = 2;
         if (members < 2) return;
     } else if (MODE == MODE_SUFFIX) {
@@ -508,6 +520,219 @@ __global__ __launch_bounds__(W *kWave) PA_OCC_ATTR void pa_decode_kernel(const D
     }
 }
 
+template <int DT, int D, int B, int W, int U, int MODE, int G>
+__global__ __launch_bounds__(W *kWave) PA_OCC_ATTR void pa_decode_kernel(const DecodeParams P)
+{
+    decode_body<DT, D, B, W, U, MODE, G>(P, (int)blockIdx.x);
+}
+
+// ---- shared-prefix decode on the matrix cores --------------------------------
+// A group's common prefix is a small dense contraction: up to 16 queries against
+// 16-token K/V tiles.  One workgroup per (group, head); wave w takes tiles
+// w, w+W, ...  Per tile:
+//   S^T = K Q^T   8 x v_mfma_f32_16x16x16 (f16 or bf16 operands, fp32 result):
+//                 A rows are tokens, B columns are queries.  Lane l supplies
+//                 row l%16; each of its four 16-byte loads feeds two MFMAs,
+//                 with the same (arbitrary but consistent) assignment of head
+//                 dimensions to contraction slots on the Q side.
+//   softmax       the result leaves lane l with query l%16 and four tokens;
+//                 the running maximum is kept per query (two cross-lane maxima
+//                 per tile), exp2 in fp32, rescaling of the output only when
+//                 some maximum moved.
+//   O += P V      32 x v_mfma_f32_16x16x4_f32: A = P in fp32 straight from the
+//                 softmax registers, B = the V fragments of the ordinary
+//                 coalesced load widened to fp32 (lane l: token l/16 + 4v,
+//                 dims 8*(l%16)+e; output column l%16 of MFMA e is dim
+//                 8*(l%16)+e).  fp32 operands keep P exact; the fp32 matrix
+//                 rate is still about three times what the HBM stream needs.
+// K rows are loaded in the order token(i) = i/4 + 4*(i%4) so that result
+// register v of lane l belongs to token l/16 + 4v, the token of V fragment v
+// in that lane: P never moves between lanes.
+// Outputs: the same unnormalised partials as MODE_PREFIX (partial 0 of 2).
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+template <int DT>
+__device__ __forceinline__ float4_t mfma_qk(uint32_t a0, uint32_t a1, uint32_t b0, uint32_t b1, float4_t c)
+{
+    const uint2 a = make_uint2(a0, a1), b = make_uint2(b0, b1);
+    if (DT == PA_F16)
+        return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4_t, a),
+                                                     __builtin_bit_cast(half4_t, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(short4_t, a),
+                                                         __builtin_bit_cast(short4_t, b), c, 0, 0, 0);
+}
+
+template <int DT>
+__device__ __forceinline__ void widen8(float (&f)[8], const uint4 &v)
+{
+    const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (DT == PA_F16) {
+            const half2_t h = __builtin_bit_cast(half2_t, u[i]);
+            f[2 * i] = (float)h.x;
+            f[2 * i + 1] = (float)h.y;
+        } else {
+            f[2 * i] = as_f32(u[i] << 16);
+            f[2 * i + 1] = as_f32(u[i] & 0xffff0000u);
+        }
+    }
+}
+
+template <int DT, int B, int W>
+__device__ __forceinline__ void prefix_mfma_body(const DecodeParams &P, const int block_index)
+{
+    constexpr int D = 128, ROW_BYTES = 256, GQ = kGroupMaxMfma;
+    constexpr int64_t TILE_BYTES = (int64_t)B * ROW_BYTES;
+    static_assert(DT != PA_F32 && B % 16 == 0, "two-byte elements, whole 16-token tiles per block");
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int r = lane / 16;
+    const int c = lane % 16;
+    const int H = P.H;
+    const int h = block_index % H;
+    const int grp = block_index / H;
+    if (grp >= P.ginfo[ginfo_shared_count(P.S)]) return;
+    const int s = P.ginfo[ginfo_shared_list(P.S, grp)];   // a group is named by its first sequence
+    const int members = P.ginfo[ginfo_group_size(P.S, s)];
+    const int t_end = P.ginfo[ginfo_group_prefix(P.S, s)];
+    if (members < 2 || t_end <= 0) return;
+    const int ntiles = t_end / 16;
+
+    // Q^T as the B operand: lane l holds, for query l%16, the same byte ranges of the
+    // query row that it will hold of each K row
+    uint4 qf[4];
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) {
+        qf[cc] = make_uint4(0, 0, 0, 0);
+        if (c < members)
+            qf[cc] = *reinterpret_cast<const uint4 *>(static_cast<const char *>(P.q) +
+                                                      ((int64_t)(s + c) * H + h) * ROW_BYTES + 64 * cc + 16 * r);
+    }
+    float4_t O[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) O[e] = float4_t{0.f, 0.f, 0.f, 0.f};
+    float m = kNegBig, lsum = 0.f;
+
+    const int32_t *__restrict__ table = P.block_tables + (int64_t)s * P.max_blocks;
+    const uint32_t k_lane_off = (uint32_t)((c / 4 + 4 * (c % 4)) * ROW_BYTES + 16 * r);
+    const uint32_t v_lane_off = (uint32_t)lane * 16u;
+
+    for (int ti = w; ti < ntiles; ti += W) {
+        const int t0 = ti * 16;
+        const int pb = table[t0 / B];
+        const int64_t base = ((int64_t)pb * H + h) * TILE_BYTES + (int64_t)(t0 % B) * ROW_BYTES;
+        uint4 kf[4], vf[4];
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) kf[cc] = load16_stream(P.k_cache + base + k_lane_off + 64 * cc);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) vf[v] = load16_stream(P.v_cache + base + v_lane_off + 1024 * v);
+
+        float4_t S = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+            S = mfma_qk<DT>(kf[cc].x, kf[cc].y, qf[cc].x, qf[cc].y, S);
+            S = mfma_qk<DT>(kf[cc].z, kf[cc].w, qf[cc].z, qf[cc].w, S);
+        }
+        float x[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) x[v] = S[v] * P.scale_log2;
+        float tmax = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float m_new = fmaxf(m, tmax);
+        if (__any(m_new > m)) {
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            lsum *= alpha;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float a = __shfl(alpha, 4 * r + v);   // output row 4r+v is query 4r+v
+#pragma unroll
+                for (int e = 0; e < 8; ++e) O[e][v] *= a;
+            }
+            m = m_new;
+        }
+        float p[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            p[v] = __builtin_amdgcn_exp2f(x[v] - m);
+            lsum += p[v];
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float vv[8];
+            widen8<DT>(vv, vf[v]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) O[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[v], vv[e], O[e], 0, 0, 0);
+        }
+    }
+    lsum += __shfl_xor(lsum, 16);
+    lsum += __shfl_xor(lsum, 32);
+
+    // merge the waves: per member, its 128 accumulators sit in the 16 lanes r = member/4
+    __shared__ float sm_acc[W][GQ][D];
+    __shared__ float sm_m[W][GQ], sm_l[W][GQ];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int qi = 4 * r + v;
+        if (qi < members && qi < GQ) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sm_acc[w][qi][8 * c + e] = O[e][v];
+        }
+    }
+    if (r == 0 && c < members && c < GQ) {
+        sm_m[w][c] = m;
+        sm_l[w][c] = lsum;
+    }
+    __syncthreads();
+    if (w != 0 || r != 0) return;
+    for (int j = 0; j < members && j < GQ; ++j) {
+        float M = sm_m[0][j];
+#pragma unroll
+        for (int i = 1; i < W; ++i) M = fmaxf(M, sm_m[i][j]);
+        float l = 0.f, acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+#pragma unroll 2
+        for (int i = 0; i < W; ++i) {
+            const float f = __builtin_amdgcn_exp2f(sm_m[i][j] - M);
+            l = __builtin_fmaf(sm_l[i][j], f, l);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = __builtin_fmaf(sm_acc[i][j][8 * c + e], f, acc[e]);
+        }
+        const int64_t slot = ((int64_t)(s + j) * H + h) * 2;
+        float *dst = P.ws_acc + slot * D + 8 * c;
+        *reinterpret_cast<float4 *>(dst) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        *reinterpret_cast<float4 *>(dst + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        if (c == 0) *reinterpret_cast<float2 *>(P.ws_ml + slot * 2) = make_float2(M, l);
+    }
+}
+
+template <int DT, int B, int W>
+__global__ __launch_bounds__(W *kWave) void pa_prefix_mfma_kernel(const DecodeParams P)
+{
+    prefix_mfma_body<DT, B, W>(P, (int)blockIdx.x);
+}
+
+// Shared prefixes and private suffixes in one launch.  The first
+// P.prefix_blocks workgroups are shared-prefix items (group, head), the rest
+// are suffix items (sequence, head); the short prefix items start first and the
+// long suffix items fill the machine around them.
+template <int DT, int B, int WS, int WP>
+__global__ __launch_bounds__(WS *kWave) PA_OCC_ATTR_FUSED void pa_shared_fused_kernel(const DecodeParams P)
+{
+    static_assert(WP == WS, "every wave of the workgroup takes part in either kind of item");
+    if ((int)blockIdx.x < P.prefix_blocks) {
+        prefix_mfma_body<DT, B, WP>(P, (int)blockIdx.x);
+    } else {
+        decode_body<DT, 128, B, WS, kChunksPerTripDevice, MODE_SUFFIX, 1>(P, (int)blockIdx.x - P.prefix_blocks);
+    }
+}
+
 // Merge of partials: out = sum_p 2^(m_p-M) a_p / sum_p 2^(m_p-M) l_p with a_p the
 // unnormalised partial sums.  One wavefront per (sequence, head); lane c
 // handles the same 16-byte output fragment as in the decode kernel.  With
@@ -570,84 +795,153 @@ __global__ __launch_bounds__(kWave) void pa_reduce_kernel(const DecodeParams P)
 // block tables start with the same physical blocks form a group (that is how
 // forked sequences sit in a batch: samples of one prompt, beams of one
 // search).  Only blocks that are full for both neighbours count, so every
-// token of a shared prefix is valid for every member.  A sequence joins the
-// current group while the group has room and the common prefix would keep at
-// least three quarters of its length; otherwise it opens a new group.
-// One workgroup; the scan over sequences is sequential and tiny.
-constexpr int kGroupMax = 4;
+// token of a shared prefix is valid for every member.
+//   adj[s] = leading blocks s has in common with s-1 (0 for s = 0).
+// A sequence with adj = 0 starts a run; runs are independent, so one thread
+// walks each run: a sequence joins the current group while the group has room
+// and the common prefix would keep at least three quarters of its length,
+// otherwise it starts a new group.  One workgroup, state in LDS when it fits.
 constexpr int kGroupScanLds = 2048;   // sequences whose scan state fits in LDS
-__global__ __launch_bounds__(256) void find_groups_kernel(const int32_t *__restrict__ block_tables,
-                                                           int32_t max_blocks,
-                                                           const int32_t *__restrict__ context_lens,
-                                                           int32_t S, int32_t block_size,
-                                                           int32_t *__restrict__ ginfo)
-{
-    // The scan state lives in LDS when it fits (the sequential part then costs a
-    // few cycles per sequence); larger batches scan in the global table itself.
-    __shared__ int32_t lds[5 * kGroupScanLds];
-    const bool in_lds = S <= kGroupScanLds;
-    int32_t *range_begin = in_lds ? lds : ginfo + ginfo_range_begin(S, 0);
-    int32_t *g_start = in_lds ? lds + S : ginfo + ginfo_group_start(S, 0);
-    int32_t *g_size = in_lds ? lds + 2 * S : ginfo + ginfo_group_size(S, 0);
-    int32_t *g_prefix = in_lds ? lds + 3 * S : ginfo + ginfo_group_prefix(S, 0);
-    int32_t *adj = in_lds ? lds + 4 * S : ginfo + ginfo_adj(S, 0);
+constexpr int kGroupThreads = 1024;
 
-    for (int s = threadIdx.x; s < S; s += 256) {
-        int a = 0;
-        if (s > 0) {
-            const int n0 = context_lens[s - 1], n1 = context_lens[s];
-            const int lim = (n0 < n1 ? n0 : n1) / block_size;
-            const int32_t *t0 = block_tables + (int64_t)(s - 1) * max_blocks;
-            const int32_t *t1 = block_tables + (int64_t)s * max_blocks;
-            while (a < lim && t0[a] == t1[a]) ++a;
+__device__ __forceinline__ void group_walk_run(const int32_t *adj, int32_t *range_begin, int32_t *g_size,
+                                               int32_t *g_prefix, int first, int S, int block_size,
+                                               int group_max)
+{
+    int start = first, size = 1, prefix = 0;
+    auto close = [&]() {
+        const int tokens = size > 1 ? prefix * block_size : 0;
+        g_size[start] = size;
+        g_prefix[start] = tokens;
+        for (int j = 0; j < size; ++j) range_begin[start + j] = tokens;
+    };
+    for (int sq = first + 1; sq < S; ++sq) {
+        const int a = adj[sq];
+        if (a == 0) break;   // the next run belongs to another thread
+        bool join = false;
+        if (size < group_max) {
+            const int np = size == 1 ? a : (a < prefix ? a : prefix);
+            join = size == 1 || 4 * np >= 3 * prefix;
+            if (join) prefix = np;
         }
-        adj[s] = a;
+        if (join) {
+            ++size;
+        } else {
+            close();
+            start = sq;
+            size = 1;
+            prefix = 0;
+        }
     }
-    __syncthreads();
-    __shared__ int32_t num_groups;
-    if (threadIdx.x == 0) {
-        int ng = 0, start = 0, size = 0, prefix = 0;
-        auto close = [&]() {
-            const int tokens = size > 1 ? prefix * block_size : 0;
-            g_start[ng] = start;
-            g_size[ng] = size;
-            g_prefix[ng] = tokens;
-            for (int j = 0; j < size; ++j) range_begin[start + j] = tokens;
-            ++ng;
-        };
-        for (int s = 0; s < S; ++s) {
-            const int a = adj[s];
-            bool join = false;
-            if (size > 0 && size < kGroupMax && a > 0) {
-                const int np = size == 1 ? a : (a < prefix ? a : prefix);
-                join = size == 1 || 4 * np >= 3 * prefix;
-                if (join) prefix = np;
+    close();
+}
+
+__global__ __launch_bounds__(kGroupThreads) void find_groups_kernel(
+    const int32_t *__restrict__ block_tables, int32_t max_blocks,
+    const int32_t *__restrict__ context_lens, int32_t S, int32_t block_size, int32_t group_max,
+    int32_t *__restrict__ ginfo)
+{
+    __shared__ int32_t s_adj[kGroupScanLds], s_range[kGroupScanLds], s_size[kGroupScanLds],
+        s_prefix[kGroupScanLds];
+    const bool in_lds = S <= kGroupScanLds;
+
+    // adj[s]: one wavefront compares the table rows of s-1 and s, 64 entries per
+    // step (lanes in parallel, first mismatch by ballot), four sequences per trip
+    // so that their loads are in flight together
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = threadIdx.x / kWave;
+    constexpr int NW = kGroupThreads / kWave, UN = 4;
+    for (int base = w * UN; base < S; base += NW * UN) {
+        int lim[UN], e0[UN], e1[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int sq = base + u;
+            lim[u] = 0;
+            if (sq > 0 && sq < S) {
+                const int n0 = context_lens[sq - 1], n1 = context_lens[sq];
+                lim[u] = (n0 < n1 ? n0 : n1) / block_size;
             }
-            if (join) {
-                ++size;
-            } else {
-                if (size > 0) close();
-                start = s;
-                size = 1;
-                prefix = 0;
+            e0[u] = e1[u] = 0;
+            if (lane < lim[u]) {
+                e0[u] = block_tables[(int64_t)(sq - 1) * max_blocks + lane];
+                e1[u] = block_tables[(int64_t)sq * max_blocks + lane];
             }
         }
-        if (size > 0) close();
-        num_groups = ng;
-        ginfo[0] = ng;
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int sq = base + u;
+            if (sq >= S) break;
+            int a = 0;
+            unsigned long long diff = __ballot(lane < lim[u] && e0[u] != e1[u]);
+            if (diff) {
+                a = __builtin_ctzll(diff);
+            } else {
+                a = lim[u] < kWave ? lim[u] : kWave;
+                // the first 64 blocks all agree: keep comparing (long shared prefixes)
+                for (int j0 = kWave; j0 < lim[u] && a == j0; j0 += kWave) {
+                    const int j = j0 + lane;
+                    bool ne = false;
+                    if (j < lim[u])
+                        ne = block_tables[(int64_t)(sq - 1) * max_blocks + j] !=
+                             block_tables[(int64_t)sq * max_blocks + j];
+                    diff = __ballot(ne);
+                    const int rest = lim[u] - j0 < kWave ? lim[u] - j0 : kWave;
+                    a = j0 + (diff ? (int)__builtin_ctzll(diff) : rest);
+                }
+            }
+            if (lane == 0) {
+                if (in_lds) {
+                    s_adj[sq] = a;
+                    s_size[sq] = 0;
+                } else {
+                    ginfo[ginfo_adj(S, sq)] = a;
+                    ginfo[ginfo_group_size(S, sq)] = 0;
+                }
+            }
+        }
     }
     __syncthreads();
     if (in_lds) {
-        const int ng = num_groups;
-        for (int i = threadIdx.x; i < S; i += 256) {
-            ginfo[ginfo_range_begin(S, i)] = range_begin[i];
-            if (i < ng) {
-                ginfo[ginfo_group_start(S, i)] = g_start[i];
-                ginfo[ginfo_group_size(S, i)] = g_size[i];
-                ginfo[ginfo_group_prefix(S, i)] = g_prefix[i];
-            }
+        for (int sq = threadIdx.x; sq < S; sq += kGroupThreads)
+            if (s_adj[sq] == 0) group_walk_run(s_adj, s_range, s_size, s_prefix, sq, S, block_size, group_max);
+        __syncthreads();
+        for (int i = threadIdx.x; i < S; i += kGroupThreads) {
+            ginfo[ginfo_range_begin(S, i)] = s_range[i];
+            ginfo[ginfo_group_size(S, i)] = s_size[i];
+            ginfo[ginfo_group_prefix(S, i)] = s_size[i] ? s_prefix[i] : 0;
         }
+    } else {
+        for (int sq = threadIdx.x; sq < S; sq += kGroupThreads)
+            if (ginfo[ginfo_adj(S, sq)] == 0)
+                group_walk_run(ginfo + ginfo_adj(S, 0), ginfo + ginfo_range_begin(S, 0),
+                               ginfo + ginfo_group_size(S, 0), ginfo + ginfo_group_prefix(S, 0), sq, S,
+                               block_size, group_max);
     }
+    __syncthreads();
+    // compact the first sequences of shared groups (two or more members), in order, so that
+    // the prefix kernel's workgroups with work come first in its grid
+    __shared__ int32_t wave_count[NW];
+    __shared__ int32_t running;
+    if (threadIdx.x == 0) running = 0;
+    __syncthreads();
+    for (int base = 0; base < S; base += kGroupThreads) {
+        const int sq = base + threadIdx.x;
+        const bool flag = sq < S && (in_lds ? s_size[sq] : ginfo[ginfo_group_size(S, sq)]) >= 2;
+        const unsigned long long mask = __ballot(flag);
+        if (lane == 0) wave_count[w] = __builtin_popcountll(mask);
+        __syncthreads();
+        int before = running;
+        for (int i = 0; i < w; ++i) before += wave_count[i];
+        if (flag) ginfo[ginfo_shared_list(S, before + __builtin_popcountll(mask & ((1ull << lane) - 1)))] = sq;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int total = running;
+            for (int i = 0; i < NW; ++i) total += wave_count[i];
+            running = total;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) ginfo[ginfo_shared_count(S)] = running;
 }
 
 // ---- reshape_and_cache -------------------------------------------------------
@@ -744,12 +1038,6 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const char *__restrict
     if (a == 0x9e3779b9u) sink[blockIdx.x & 65535] = a;
 }
 
-// chunks requested together per trip of the steady-state loop
-#ifndef PA_CHUNKS_PER_TRIP
-#define PA_CHUNKS_PER_TRIP 2
-#endif
-constexpr int kChunksPerTrip = PA_CHUNKS_PER_TRIP;
-
 // ---- host side -----------------------------------------------------------------
 int elem_bytes(pa_dtype dt) { return dt == PA_F32 ? 4 : 2; }
 
@@ -792,19 +1080,30 @@ void dispatch_mode(const DecodeArgs &a, int mode)
         hipLaunchKernelGGL((pa_reduce_kernel<DT, D, false>), dim3(rows), dim3(kWave), 0, a.stream, a.p);
     } else if (mode == MODE_PREFIX) {
         // shared-prefix path: group table, prefixes once per group, private suffixes, merge
-        hipLaunchKernelGGL(find_groups_kernel, dim3(1), dim3(256), 0, a.stream, a.p.block_tables,
-                           a.p.max_blocks, a.p.context_lens, a.p.S, B, const_cast<int32_t *>(a.p.ginfo));
-#ifdef PA_TUNE_PREFIX_W
-        launch_decode_kernel<DT, D, B, PA_TUNE_PREFIX_W, MODE_PREFIX, kGroupMax>(a, S);
-#else
-        launch_decode_kernel<DT, D, B, 8, MODE_PREFIX, kGroupMax>(a, S);
-#endif
-        if (a.waves >= 16)
-            launch_decode_kernel<DT, D, B, 16, MODE_SUFFIX>(a, S);
-        else if (a.waves >= 8)
-            launch_decode_kernel<DT, D, B, 8, MODE_SUFFIX>(a, S);
-        else
-            launch_decode_kernel<DT, D, B, 4, MODE_SUFFIX>(a, S);
+        constexpr bool kMfma = DT != PA_F32 && D == 128 && B % 16 == 0;
+        hipLaunchKernelGGL(find_groups_kernel, dim3(1), dim3(kGroupThreads), 0, a.stream, a.p.block_tables,
+                           a.p.max_blocks, a.p.context_lens, a.p.S, B, kMfma ? kGroupMaxMfma : kGroupMax,
+                           const_cast<int32_t *>(a.p.ginfo));
+        if constexpr (kMfma) {
+            // a shared group has two or more members: at most S/2 groups
+            DecodeArgs f = a;
+            f.p.prefix_blocks = (int32_t)(((S + 1) / 2) * (unsigned)a.p.H);
+            const unsigned blocks = (unsigned)f.p.prefix_blocks + rows;
+            // eight waves per workgroup: two workgroups share a compute unit, so a short prefix
+            // item's load latency is covered by a streaming suffix item (measured better than sixteen)
+            if (a.waves >= 8)
+                hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 8, 8>), dim3(blocks), dim3(8 * kWave), 0, a.stream, f.p);
+            else
+                hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 4, 4>), dim3(blocks), dim3(4 * kWave), 0, a.stream, f.p);
+        } else {
+            launch_decode_kernel<DT, D, B, 8, MODE_PREFIX, kGroupMax>(a, S);
+            if (a.waves >= 16)
+                launch_decode_kernel<DT, D, B, 16, MODE_SUFFIX>(a, S);
+            else if (a.waves >= 8)
+                launch_decode_kernel<DT, D, B, 8, MODE_SUFFIX>(a, S);
+            else
+                launch_decode_kernel<DT, D, B, 4, MODE_SUFFIX>(a, S);
+        }
         hipLaunchKernelGGL((pa_reduce_kernel<DT, D, true>), dim3(rows), dim3(kWave), 0, a.stream, a.p);
     } else {
         switch (a.waves) {

@@ -141,6 +141,12 @@ def test_shared_decode_fully_shared_and_mixed(pa):
     seqs += [b] + kids                                        # group of 5 -> 4 + 1
     c = mgr.allocate(16)
     seqs += [c, mgr.fork(c)]                                  # exactly one shared full block, nothing else
+    d = mgr.allocate(150)
+    many = [d] + [mgr.fork(d) for _ in range(9)]              # ten forks: more than one group can hold
+    for i, sq in enumerate(many):
+        for _ in range(3 * i):
+            mgr.append(sq)
+    seqs += many
     mgr.take_copies()
     for dtype in ("f16", "bf16"):
         filled = np.zeros((NB, B), dtype=bool)
