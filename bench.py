@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--block-size-sweep", action="store_true",
                     help="instead of the step benchmark: pa_decode at the OPT-13B shape for B = 8..128")
+    ap.add_argument("--multi-query", action="store_true",
+                    help="instead of the step benchmark: pa_decode_multi at the OPT-13B shape for several q_len")
     ap.add_argument("--cache-ops", action="store_true",
                     help="instead of the step benchmark: pa_reshape_and_cache and pa_copy_blocks at several sizes")
     return ap.parse_args()
@@ -103,6 +105,39 @@ def block_size_sweep(pa, W, np, torch, dev):
         del kc, vc
     print(json.dumps({"metric": "pa_decode_block_size_sweep", "workload": "OPT-13B shape, 64 seq, ctx U{1..2048}, fp16",
                       "rows": rows}))
+
+
+def multi_query(pa, W, np, torch, dev):
+    """pa_decode_multi at the OPT-13B layer shape: every sequence brings its last q_len tokens as queries.
+    K/V of a sequence is read once per block of 16 queries, so KV bytes = sum_s ceil(q_len_s/16)*ctx_s*H*2*D*E."""
+    rng = np.random.default_rng(2000)
+    lens = rng.integers(1, 2049, size=64)
+    w = W.independent_sequences("opt13b_multi", "f16", 40, 128, 16, lens, 2001)
+    H, D, B = 40, 128, 16
+    kc = torch.randn((w.num_blocks, H, B, D), dtype=torch.float16, device=dev)
+    vc = torch.randn_like(kc)
+    bt = torch.from_numpy(w.block_tables).to(dev)
+    cl = torch.from_numpy(w.context_lens).to(dev)
+    rows = []
+    for qmax in (1, 4, 16, 64, 256):
+        ql = np.minimum(lens, qmax)
+        qs = np.concatenate([[0], np.cumsum(ql)]).astype(np.int32)
+        T = int(qs[-1])
+        q = torch.randn((T, H, D), dtype=torch.float16, device=dev)
+        out = torch.empty_like(q)
+        dqs = torch.from_numpy(qs).to(dev)
+        us = _time_us(lambda: pa.pa_decode_multi(out, q, kc, vc, bt, cl, dqs, qmax, B, float(w.scale),
+                                                 w.max_context_len), 50, torch)
+        kv = int((((ql + 15) // 16) * lens).sum()) * H * D * 2 * 2
+        rows.append({"max_q_len": qmax, "query_tokens": T, "us": us, "query_tokens_per_s": T / us * 1e6,
+                     "kv_GBps": kv / us / 1e3})
+    q1 = torch.randn((64, H, D), dtype=torch.float16, device=dev)
+    o1 = torch.empty_like(q1)
+    us = _time_us(lambda: pa.pa_decode(o1, q1, kc, vc, bt, cl, B, float(w.scale), w.max_context_len, 0, None),
+                  50, torch)
+    print(json.dumps({"metric": "pa_decode_multi", "workload": "OPT-13B shape, 64 seq, ctx U{1..2048}, fp16, "
+                      "q_len = min(ctx, max_q_len)", "rows": rows,
+                      "pa_decode_one_query": {"us": us, "kv_GBps": w.kv_bytes_logical() / us / 1e3}}))
 
 
 def cache_ops(pa, np, torch, dev):
@@ -169,6 +204,8 @@ def main():
         return block_size_sweep(pa, W, np, torch, dev)
     if args.cache_ops:
         return cache_ops(pa, np, torch, dev)
+    if args.multi_query:
+        return multi_query(pa, W, np, torch, dev)
 
     make = {"cfg1": W.config1, "cfg2": W.config2, "cfg3": W.config3, "cfg4": W.config4,
             "cfg5": W.config5}[args.workload]

@@ -136,6 +136,30 @@ pa_status pa_decode_shared(void *out, const void *q, const void *k_cache, const 
 size_t pa_decode_shared_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t head_dim);
 
 /*
+ * pa_decode_multi - several query tokens per sequence over the paged cache:
+ * the case where only the tail of a prompt has to be computed because its
+ * prefix is already cached (Sec. 4.4, "Shared prefix"), or a few draft tokens
+ * to be checked at once.  Sequence s contributes q_len_s = q_start[s+1] -
+ * q_start[s] query rows, the last q_len_s tokens of its context (their K/V
+ * must already be in the cache, as for pa_decode).  Query i of them, at
+ * position n_s - q_len_s + i, attends to tokens 0 .. n_s - q_len_s + i
+ * (causal), by the same formula as pa_decode; q_len_s = 1 is pa_decode.
+ * Runs on the matrix cores, 16 queries per workgroup; K/V of a sequence is read
+ * once per 16 queries.
+ *
+ *   out, q        [q_start[S]][H][D] dtype, rows of sequence s at q_start[s] ..
+ *   q_start       device [S+1] int32, non-decreasing, q_start[0] = 0
+ *   max_q_len     host-known upper bound on q_len_s; q_len_s <= context_lens[s]
+ * Supported: f16 / bf16, head_dim 128, block_size a multiple of 16.
+ */
+pa_status pa_decode_multi(void *out, const void *q, const void *k_cache, const void *v_cache,
+                          const int32_t *block_tables, int32_t max_blocks_per_seq,
+                          const int32_t *context_lens, const int32_t *q_start, int32_t num_seqs,
+                          int32_t max_q_len, int32_t num_heads, int32_t head_dim,
+                          int32_t block_size, int64_t num_blocks, pa_dtype dtype, float scale,
+                          int32_t max_context_len, void *stream);
+
+/*
  * pa_reshape_and_cache - store new K/V vectors into the paged cache
  * (Sec. 4.3: the KV of the tokens of this iteration is saved into the
  * physical blocks; Sec. 5.1 (1): reshape and block write fused in one launch).

@@ -45,6 +45,9 @@ def _load():
         lib.pa_oracle_decode.restype = ctypes.c_int
         lib.pa_oracle_decode.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i32,
                                          ctypes.c_float, i32, vp, i64, i32]
+        lib.pa_oracle_decode_multi.restype = ctypes.c_int
+        lib.pa_oracle_decode_multi.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32,
+                                               ctypes.c_float, i32]
         lib.pa_oracle_reshape_and_cache.restype = None
         lib.pa_oracle_reshape_and_cache.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32]
         lib.pa_oracle_copy_blocks.restype = None
@@ -93,6 +96,27 @@ def decode(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, block_tables
                                     S, H, D, B, DTYPE_CODE[dtype], float(np.float32(scale)),
                                     int(partition_size), rp, nrows, int(threads))
     return (out, used) if return_threads else out
+
+
+def decode_multi(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, block_tables: np.ndarray,
+                 context_lens: np.ndarray, q_start: np.ndarray, scale, dtype: str, threads: int = 0):
+    """fp64 causal attention [T][H][D] of each sequence's last q_len tokens (rows q_start[s]..q_start[s+1])."""
+    st = _NP_OF[dtype]
+    _chk(q, st, "q"); _chk(k_cache, st, "k_cache"); _chk(v_cache, st, "v_cache")
+    _chk(block_tables, np.int32, "block_tables"); _chk(context_lens, np.int32, "context_lens")
+    _chk(q_start, np.int32, "q_start")
+    T, H, D = q.shape
+    NB, H2, B, D2 = k_cache.shape
+    S = context_lens.shape[0]
+    assert (H2, D2) == (H, D) and v_cache.shape == k_cache.shape
+    assert q_start.shape == (S + 1,) and q_start[0] == 0 and q_start[-1] == T
+    q_len = np.diff(q_start)
+    assert (q_len >= 0).all() and (q_len <= context_lens).all()
+    out = np.empty((T, H, D), dtype=np.float64)
+    _load().pa_oracle_decode_multi(_ptr(out), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+                                   block_tables.shape[1], _ptr(context_lens), _ptr(q_start), S, H, D, B,
+                                   DTYPE_CODE[dtype], float(np.float32(scale)), int(threads))
+    return out
 
 
 def reshape_and_cache(k: np.ndarray, v: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,

@@ -141,12 +141,15 @@ static void attend(double *o, double *m_out, double *l_out, const double *qd, co
     free(x);
 }
 
-static void decode_row(double *o, const void *q, const void *k_cache, const void *v_cache,
-                       const int32_t *block_tables, int32_t max_blocks_per_seq,
-                       const int32_t *context_lens, int s, int h, int H, int D, int B, int dtype,
-                       float scale, int partition_size)
+/*
+ * One output row: query row `qrow` of q ([rows][H][D]), head h, attending to the
+ * first n tokens of sequence s.
+ */
+static void decode_row(double *o, const void *q, int64_t qrow, const void *k_cache,
+                       const void *v_cache, const int32_t *block_tables,
+                       int32_t max_blocks_per_seq, int n, int s, int h, int H, int D, int B,
+                       int dtype, float scale, int partition_size)
 {
-    int n = context_lens[s];
     if (n <= 0) {
         for (int d = 0; d < D; ++d)
             o[d] = 0.0;
@@ -155,7 +158,7 @@ static void decode_row(double *o, const void *q, const void *k_cache, const void
     const int32_t *row = block_tables + (int64_t)s * max_blocks_per_seq;
     double *qd = (double *)malloc(sizeof(double) * (size_t)D);
     for (int d = 0; d < D; ++d)
-        qd[d] = load_elem(q, ((int64_t)s * H + h) * D + d, dtype);
+        qd[d] = load_elem(q, (qrow * H + h) * D + d, dtype);
     double *Kc = (double *)malloc(sizeof(double) * (size_t)n * D);
     double *Vc = (double *)malloc(sizeof(double) * (size_t)n * D);
     gather_kv(Kc, Vc, k_cache, v_cache, row, 0, n, h, H, D, B, dtype);
@@ -218,9 +221,45 @@ int pa_oracle_decode(double *out, const void *q, const void *k_cache, const void
     for (int64_t r = 0; r < num_rows; ++r) {
         int s = rows ? rows[2 * r] : (int)(r / num_heads);
         int h = rows ? rows[2 * r + 1] : (int)(r % num_heads);
-        decode_row(out + r * head_dim, q, k_cache, v_cache, block_tables, max_blocks_per_seq,
-                   context_lens, s, h, num_heads, head_dim, block_size, dtype, scale,
+        decode_row(out + r * head_dim, q, s, k_cache, v_cache, block_tables, max_blocks_per_seq,
+                   context_lens[s], s, h, num_heads, head_dim, block_size, dtype, scale,
                    partition_size);
+    }
+    return used;
+}
+
+/*
+ * Several query tokens per sequence: the prompt phase restricted to the part of
+ * a prompt that follows an already cached prefix (Sec. 4.4, shared prefix).
+ * Sequence s has q_len = q_start[s+1] - q_start[s] query rows, its last q_len
+ * tokens; the query at position i (0-based in the whole sequence) attends to
+ * positions 0..i, which is Eq. "attention-layer" of Sec. 2.1 with its own i.
+ * out is [q_start[S]][H][D] in fp64.
+ */
+int pa_oracle_decode_multi(double *out, const void *q, const void *k_cache, const void *v_cache,
+                           const int32_t *block_tables, int32_t max_blocks_per_seq,
+                           const int32_t *context_lens, const int32_t *q_start, int32_t num_seqs,
+                           int32_t num_heads, int32_t head_dim, int32_t block_size, int32_t dtype,
+                           float scale, int32_t threads)
+{
+    int used = 1;
+    int64_t total = (int64_t)q_start[num_seqs] * num_heads;
+#ifdef _OPENMP
+    if (threads <= 0)
+        threads = omp_get_max_threads();
+    used = threads;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(threads)
+#endif
+    for (int64_t r = 0; r < total; ++r) {
+        int64_t row = r / num_heads;
+        int h = (int)(r % num_heads);
+        int s = 0;
+        while (q_start[s + 1] <= row)
+            ++s;
+        int q_len = q_start[s + 1] - q_start[s];
+        int pos = context_lens[s] - q_len + (int)(row - q_start[s]);   /* the query's own position */
+        decode_row(out + r * head_dim, q, row, k_cache, v_cache, block_tables, max_blocks_per_seq,
+                   pos + 1, s, h, num_heads, head_dim, block_size, dtype, scale, 0);
     }
     return used;
 }

@@ -18,7 +18,7 @@ from .build import LIB
 PA_F32, PA_F16, PA_BF16 = 0, 1, 2
 PA_PARTITION_AUTO = -1
 
-EXPORTS = ("pa_decode", "pa_decode_workspace_bytes", "pa_decode_shared", "pa_decode_shared_workspace_bytes", "pa_reshape_and_cache", "pa_copy_blocks", "pa_swap_blocks",
+EXPORTS = ("pa_decode", "pa_decode_workspace_bytes", "pa_decode_shared", "pa_decode_shared_workspace_bytes", "pa_decode_multi", "pa_reshape_and_cache", "pa_copy_blocks", "pa_swap_blocks",
            "pa_debug_validate", "pa_stream_read", "pa_status_string", "pa_version")
 
 _DT = {torch.float32: PA_F32, torch.float16: PA_F16, torch.bfloat16: PA_BF16}
@@ -52,6 +52,9 @@ def load_library() -> ctypes.CDLL:
                                      ctypes.c_float, i32, vp, sz, vp]
     lib.pa_decode_shared_workspace_bytes.restype = sz
     lib.pa_decode_shared_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.pa_decode_multi.restype = ctypes.c_int
+    lib.pa_decode_multi.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i64, ctypes.c_int,
+                                    ctypes.c_float, i32, vp]
     lib.pa_reshape_and_cache.restype = ctypes.c_int
     lib.pa_reshape_and_cache.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, ctypes.c_int, vp]
     lib.pa_copy_blocks.restype = ctypes.c_int
@@ -141,6 +144,25 @@ def pa_decode_shared(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, 
         block_tables.shape[1], _dev(context_lens, "context_lens", torch.int32), S, H, D, B, NB,
         _DT[q.dtype], float(scale), int(max_context_len), _dev(workspace, "workspace"),
         workspace.numel() * workspace.element_size(), _stream()))
+
+
+def pa_decode_multi(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                    block_tables: torch.Tensor, context_lens: torch.Tensor, q_start: torch.Tensor,
+                    max_q_len: int, block_size: int, scale: float, max_context_len: int) -> None:
+    """out[T][H][D]: causal attention of each sequence's last q_len tokens (rows q_start[s]..q_start[s+1])."""
+    T, H, D = q.shape
+    NB, H2, B, D2 = k_cache.shape
+    S = context_lens.shape[0]
+    if (H2, B, D2) != (H, block_size, D) or v_cache.shape != k_cache.shape or out.shape != q.shape:
+        raise ValueError("inconsistent shapes")
+    if block_tables.dim() != 2 or block_tables.shape[0] != S or q_start.shape != (S + 1,):
+        raise ValueError("block_tables must be [S][MB], q_start [S+1]")
+    _check(load_library().pa_decode_multi(
+        _dev(out, "out", q.dtype) if T else None, _dev(q, "q") if T else None,
+        _dev(k_cache, "k_cache", q.dtype), _dev(v_cache, "v_cache", q.dtype),
+        _dev(block_tables, "block_tables", torch.int32), block_tables.shape[1],
+        _dev(context_lens, "context_lens", torch.int32), _dev(q_start, "q_start", torch.int32), S,
+        int(max_q_len), H, D, B, NB, _DT[q.dtype], float(scale), int(max_context_len), _stream()))
 
 
 def pa_reshape_and_cache(k: torch.Tensor, v: torch.Tensor, k_cache: torch.Tensor,

@@ -179,9 +179,6 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 // call, and streaming them past the caches measurably raises the HBM rate.
 __device__ __forceinline__ uint4 load16_stream(const char *p)
 {
-#ifdef PA_PLAIN_LOADS
-    return *reinterpret_cast<const uint4 *>(p);
-#endif
     const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
     return make_uint4(v.x, v.y, v.z, v.w);
 }
@@ -236,10 +233,12 @@ struct DecodeParams {
     const int32_t *block_tables;
     const int32_t *context_lens;
     const int32_t *ginfo;   // group table built by find_groups_kernel (shared-prefix path)
+    const int32_t *q_start; // multi-query path: first query row of every sequence, [S+1]
     float *ws_acc, *ws_ml;
     int32_t max_blocks, S, H;
     int32_t partition_size, max_parts;
     int32_t prefix_blocks;   // fused shared-prefix launch: workgroups [0, prefix_blocks) are prefix items
+    int32_t q_blocks;        // multi-query path: blocks of 16 queries per sequence in the grid
     float scale_log2;
 };
 
@@ -256,15 +255,11 @@ __device__ __host__ __forceinline__ int ginfo_shared_list(int S, int i) { return
 __device__ __host__ __forceinline__ int ginfo_shared_count(int S) { return 5 * S; }
 __device__ __host__ __forceinline__ size_t ginfo_words(int S) { return 5 * (size_t)S + 4; }
 
-#ifdef PA_TUNE_OCC
-#define PA_OCC_ATTR __attribute__((amdgpu_waves_per_eu(PA_TUNE_OCC, PA_TUNE_OCC)))
-#else
 // A sixteen-wave workgroup is kept alone on its compute unit (at most 7 waves
 // per SIMD, so a second one does not fit): measured on batches of mixed
 // lengths, two resident workgroups each run at half speed and stretch the end
 // of the launch by more than their overlap gains.
 #define PA_OCC_ATTR __attribute__((amdgpu_waves_per_eu(W == 16 ? 4 : 1, W == 16 ? 7 : 8)))
-#endif
 #define PA_OCC_ATTR_FUSED __attribute__((amdgpu_waves_per_eu(WS == 16 ? 4 : 1, WS == 16 ? 7 : 8)))
 template <int DT, int D, int B, int W, int U, int MODE, int G>
 __device__ __forceinline__ void decode_body(const DecodeParams &P, const int block_index)
@@ -582,12 +577,18 @@ __device__ __forceinline__ void widen8(float (&f)[8], const uint4 &v)
     }
 }
 
-template <int DT, int B, int W>
+// MULTI = false: a group's shared prefix (GQ = 8 query slots, partial results).
+// MULTI = true:  the last q_len tokens of ONE sequence as queries over its whole
+//                context, 16 per workgroup, with the causal rule that query i of the
+//                q_len new tokens sees tokens 0 .. n - q_len + i; writes output rows.
+template <int DT, int B, int W, int GQ, bool MULTI>
 __device__ __forceinline__ void prefix_mfma_body(const DecodeParams &P, const int block_index)
 {
-    constexpr int D = 128, ROW_BYTES = 256, GQ = kGroupMaxMfma;
+    using Tr = Traits<DT>;
+    constexpr int D = 128, ROW_BYTES = 256;
     constexpr int64_t TILE_BYTES = (int64_t)B * ROW_BYTES;
     static_assert(DT != PA_F32 && B % 16 == 0, "two-byte elements, whole 16-token tiles per block");
+    static_assert(GQ <= 16, "one MFMA row per query");
 
     const int lane = threadIdx.x & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -595,13 +596,40 @@ __device__ __forceinline__ void prefix_mfma_body(const DecodeParams &P, const in
     const int c = lane % 16;
     const int H = P.H;
     const int h = block_index % H;
-    const int grp = block_index / H;
-    if (grp >= P.ginfo[ginfo_shared_count(P.S)]) return;
-    const int s = P.ginfo[ginfo_shared_list(P.S, grp)];   // a group is named by its first sequence
-    const int members = P.ginfo[ginfo_group_size(P.S, s)];
-    const int t_end = P.ginfo[ginfo_group_prefix(P.S, s)];
-    if (members < 2 || t_end <= 0) return;
-    const int ntiles = t_end / 16;
+    const int rest = block_index / H;
+
+    // s: sequence whose table is walked; query c of this item is row q_row0 + c*q_row_step
+    // of P.q; tokens [0, t_hi) are visited; token t counts for query c iff t <= limit
+    int s, members, t_hi, t_lo, limit;
+    int64_t q_row0, q_row_step;
+    if (MULTI) {
+        const int qb = rest % P.q_blocks;
+        s = rest / P.q_blocks;
+        const int n = P.context_lens[s];
+        const int qs = P.q_start[s];
+        const int qlen = P.q_start[s + 1] - qs;
+        const int q0 = qb * 16;
+        if (q0 >= qlen || n <= 0) return;
+        members = qlen - q0 < 16 ? qlen - q0 : 16;
+        t_lo = n - qlen + q0 + 1;            // tokens the first query of the item sees
+        t_hi = t_lo + members - 1;           // tokens the last one sees
+        if (t_hi > n) t_hi = n;
+        limit = c < members ? t_lo - 1 + c : -1;
+        q_row0 = qs + q0;
+        q_row_step = 1;
+    } else {
+        if (rest >= P.ginfo[ginfo_shared_count(P.S)]) return;
+        s = P.ginfo[ginfo_shared_list(P.S, rest)];   // a group is named by its first sequence
+        members = P.ginfo[ginfo_group_size(P.S, s)];
+        t_hi = P.ginfo[ginfo_group_prefix(P.S, s)];
+        if (members < 2 || t_hi <= 0) return;
+        if (members > GQ) members = GQ;
+        t_lo = t_hi;                          // every member sees every token of the prefix
+        limit = 0x7fffffff;
+        q_row0 = s;
+        q_row_step = 1;
+    }
+    const int ntiles = (t_hi + 15) / 16;
 
     // Q^T as the B operand: lane l holds, for query l%16, the same byte ranges of the
     // query row that it will hold of each K row
@@ -611,7 +639,8 @@ __device__ __forceinline__ void prefix_mfma_body(const DecodeParams &P, const in
         qf[cc] = make_uint4(0, 0, 0, 0);
         if (c < members)
             qf[cc] = *reinterpret_cast<const uint4 *>(static_cast<const char *>(P.q) +
-                                                      ((int64_t)(s + c) * H + h) * ROW_BYTES + 64 * cc + 16 * r);
+                                                      ((q_row0 + c * q_row_step) * H + h) * ROW_BYTES +
+                                                      64 * cc + 16 * r);
     }
     float4_t O[8];
 #pragma unroll
@@ -641,6 +670,21 @@ __device__ __forceinline__ void prefix_mfma_body(const DecodeParams &P, const in
         float x[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) x[v] = S[v] * P.scale_log2;
+        if (MULTI && t0 + 16 > t_lo) {
+            // the tile reaches past what the first query sees: apply the causal rule per
+            // (query, token), and clear V rows no query of the item sees (they may lie
+            // past the context and hold anything) - by select, never by multiplying
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int tok = t0 + r + 4 * v;
+                x[v] = tok <= limit ? x[v] : -INFINITY;
+                const bool unseen = tok >= t_hi;
+                vf[v].x = unseen ? 0u : vf[v].x;
+                vf[v].y = unseen ? 0u : vf[v].y;
+                vf[v].z = unseen ? 0u : vf[v].z;
+                vf[v].w = unseen ? 0u : vf[v].w;
+            }
+        }
         float tmax = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
         tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
@@ -673,24 +717,24 @@ __device__ __forceinline__ void prefix_mfma_body(const DecodeParams &P, const in
     lsum += __shfl_xor(lsum, 16);
     lsum += __shfl_xor(lsum, 32);
 
-    // merge the waves: per member, its 128 accumulators sit in the 16 lanes r = member/4
+    // merge the waves: per query, its 128 accumulators sit in the 16 lanes r = query/4
     __shared__ float sm_acc[W][GQ][D];
     __shared__ float sm_m[W][GQ], sm_l[W][GQ];
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         const int qi = 4 * r + v;
-        if (qi < members && qi < GQ) {
+        if (qi < members) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) sm_acc[w][qi][8 * c + e] = O[e][v];
         }
     }
-    if (r == 0 && c < members && c < GQ) {
+    if (r == 0 && c < members) {
         sm_m[w][c] = m;
         sm_l[w][c] = lsum;
     }
     __syncthreads();
     if (w != 0 || r != 0) return;
-    for (int j = 0; j < members && j < GQ; ++j) {
+    for (int j = 0; j < members; ++j) {
         float M = sm_m[0][j];
 #pragma unroll
         for (int i = 1; i < W; ++i) M = fmaxf(M, sm_m[i][j]);
@@ -704,18 +748,28 @@ __device__ __forceinline__ void prefix_mfma_body(const DecodeParams &P, const in
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[e] = __builtin_fmaf(sm_acc[i][j][8 * c + e], f, acc[e]);
         }
-        const int64_t slot = ((int64_t)(s + j) * H + h) * 2;
-        float *dst = P.ws_acc + slot * D + 8 * c;
-        *reinterpret_cast<float4 *>(dst) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        *reinterpret_cast<float4 *>(dst + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
-        if (c == 0) *reinterpret_cast<float2 *>(P.ws_ml + slot * 2) = make_float2(M, l);
+        if (MULTI) {
+            const float inv = 1.0f / l;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] *= inv;
+            reinterpret_cast<uint4 *>(P.out)[((q_row0 + j) * H + h) * 16 + c] = Tr::pack(acc);
+        } else {
+            const int64_t slot = ((int64_t)(s + j) * H + h) * 2;
+            float *dst = P.ws_acc + slot * D + 8 * c;
+            *reinterpret_cast<float4 *>(dst) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            *reinterpret_cast<float4 *>(dst + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+            if (c == 0) *reinterpret_cast<float2 *>(P.ws_ml + slot * 2) = make_float2(M, l);
+        }
     }
 }
 
+// Several query tokens per sequence (the tail of a prompt over an already cached
+// prefix, Sec. 4.4 "shared prefix"; or draft tokens to verify): grid =
+// (sequence, block of 16 queries, head).
 template <int DT, int B, int W>
-__global__ __launch_bounds__(W *kWave) void pa_prefix_mfma_kernel(const DecodeParams P)
+__global__ __launch_bounds__(W *kWave) void pa_decode_multi_kernel(const DecodeParams P)
 {
-    prefix_mfma_body<DT, B, W>(P, (int)blockIdx.x);
+    prefix_mfma_body<DT, B, W, 16, true>(P, (int)blockIdx.x);
 }
 
 // Shared prefixes and private suffixes in one launch.  The first
@@ -727,7 +781,7 @@ __global__ __launch_bounds__(WS *kWave) PA_OCC_ATTR_FUSED void pa_shared_fused_k
 {
     static_assert(WP == WS, "every wave of the workgroup takes part in either kind of item");
     if ((int)blockIdx.x < P.prefix_blocks) {
-        prefix_mfma_body<DT, B, WP>(P, (int)blockIdx.x);
+        prefix_mfma_body<DT, B, WP, kGroupMaxMfma, false>(P, (int)blockIdx.x);
     } else {
         decode_body<DT, 128, B, WS, kChunksPerTripDevice, MODE_SUFFIX, 1>(P, (int)blockIdx.x - P.prefix_blocks);
     }
@@ -1110,11 +1164,7 @@ void dispatch_mode(const DecodeArgs &a, int mode)
         case 2: launch_decode_kernel<DT, D, B, 2, MODE_SINGLE>(a, S); break;
         case 4: launch_decode_kernel<DT, D, B, 4, MODE_SINGLE>(a, S); break;
         case 8: launch_decode_kernel<DT, D, B, 8, MODE_SINGLE>(a, S); break;
-#ifdef PA_TUNE_W
-        default: launch_decode_kernel<DT, D, B, PA_TUNE_W, MODE_SINGLE>(a, S); break;
-#else
         default: launch_decode_kernel<DT, D, B, 16, MODE_SINGLE>(a, S); break;
-#endif
         }
     }
 }
@@ -1147,9 +1197,10 @@ bool dispatch_decode(const DecodeArgs &a, pa_dtype dt, int D, int B, int mode)
 // Measured on MI355X at the OPT-13B shape: a workgroup should have about one
 // wave per four chunks of its longest possible item - fewer waves leave the end
 // of the launch to a few slow workgroups, more waves cost launch time that
-// short items cannot pay back.  Splitting the context costs 3-8% (workspace
-// traffic, empty workgroups, the second kernel) and pays only when there are
-// too few (sequence, head) pairs to fill the compute units.
+// short items cannot pay back.  Splitting the context costs 3-8% at large
+// batches (workspace traffic, empty workgroups, the second kernel) and pays
+// when there are too few (sequence, head) pairs to fill the compute units
+// evenly (one sequence of 8192 tokens: 79 us in one pass, 31 us split).
 int compute_units()
 {
     static int cached = 0;
@@ -1182,13 +1233,32 @@ int waves_for(int tokens_per_item, int ct)
 
 int auto_partition(int S, int H, int max_context_len)
 {
+    // One pass when there are at least four (sequence, head) items per compute unit.
+    // Fewer items leave units idle or the last round of workgroups mostly empty
+    // (8 sequences x 40 heads x 2048 tokens: 61 us in one pass, 53 us split), so
+    // the context is cut until there are about four items per unit, in ranges of
+    // at least 512 tokens (a multiple of every supported block size).
     const int cus = compute_units();
     const int64_t items = (int64_t)S * H;
-    if (items >= 2 * (int64_t)cus || max_context_len <= 512) return 0;
+    if (items >= 4 * (int64_t)cus || max_context_len <= 512) return 0;
     const int64_t want_parts = (4 * (int64_t)cus + items - 1) / items;
     int64_t ps = (max_context_len + want_parts - 1) / want_parts;
-    ps = ((ps + 255) / 256) * 256;   // a multiple of every supported block size
+    ps = ((ps + 255) / 256) * 256;
+    if (ps < 512) ps = 512;
     return ps >= max_context_len ? 0 : (int)ps;
+}
+
+template <int DT>
+bool launch_multi(const DecodeArgs &a, int B, unsigned blocks)
+{
+    constexpr int W = 4;   // 16 query rows of partial results per wave: four waves fill 32 KiB of LDS
+    switch (B) {
+    case 16: hipLaunchKernelGGL((pa_decode_multi_kernel<DT, 16, W>), dim3(blocks), dim3(W * kWave), 0, a.stream, a.p); return true;
+    case 32: hipLaunchKernelGGL((pa_decode_multi_kernel<DT, 32, W>), dim3(blocks), dim3(W * kWave), 0, a.stream, a.p); return true;
+    case 64: hipLaunchKernelGGL((pa_decode_multi_kernel<DT, 64, W>), dim3(blocks), dim3(W * kWave), 0, a.stream, a.p); return true;
+    case 128: hipLaunchKernelGGL((pa_decode_multi_kernel<DT, 128, W>), dim3(blocks), dim3(W * kWave), 0, a.stream, a.p); return true;
+    }
+    return false;
 }
 
 void fill_common(DecodeArgs &a, void *out, const void *q, const void *k_cache, const void *v_cache,
@@ -1323,6 +1393,38 @@ pa_status pa_decode_shared(void *out, const void *q, const void *k_cache, const 
     a.p.ws_ml = a.p.ws_acc + rows2 * head_dim;
     a.p.ginfo = reinterpret_cast<const int32_t *>(a.p.ws_ml + rows2 * 2);
     if (!dispatch_decode(a, dtype, head_dim, block_size, MODE_PREFIX)) return PA_ERR_UNSUPPORTED;
+    return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
+}
+
+pa_status pa_decode_multi(void *out, const void *q, const void *k_cache, const void *v_cache,
+                          const int32_t *block_tables, int32_t max_blocks_per_seq,
+                          const int32_t *context_lens, const int32_t *q_start, int32_t num_seqs,
+                          int32_t max_q_len, int32_t num_heads, int32_t head_dim, int32_t block_size,
+                          int64_t num_blocks, pa_dtype dtype, float scale, int32_t max_context_len,
+                          void *stream)
+{
+    if (num_seqs < 0 || num_heads <= 0 || head_dim <= 0 || block_size <= 0 || num_blocks <= 0 ||
+        max_blocks_per_seq <= 0 || max_context_len < 0 || max_q_len < 0)
+        return PA_ERR_SHAPE;
+    if ((dtype != PA_F16 && dtype != PA_BF16) || head_dim != 128 || block_size % 16 ||
+        !shape_supported(dtype, head_dim, block_size))
+        return PA_ERR_UNSUPPORTED;
+    if ((int64_t)max_context_len > (int64_t)max_blocks_per_seq * block_size) return PA_ERR_SHAPE;
+    if (num_seqs == 0 || max_q_len == 0) return PA_OK;
+    if (!out || !q || !k_cache || !v_cache || !block_tables || !context_lens || !q_start) return PA_ERR_NULL;
+    if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return PA_ERR_ALIGN;
+    const int64_t q_blocks = (max_q_len + 15) / 16;
+    const int64_t blocks = (int64_t)num_seqs * q_blocks * num_heads;
+    if (blocks > 0x7fffffff) return PA_ERR_SHAPE;
+    DecodeArgs a;
+    memset(&a, 0, sizeof(a));
+    fill_common(a, out, q, k_cache, v_cache, block_tables, max_blocks_per_seq, context_lens, num_seqs,
+                num_heads, scale, stream);
+    a.p.q_start = q_start;
+    a.p.q_blocks = (int32_t)q_blocks;
+    const bool ok = dtype == PA_F16 ? launch_multi<PA_F16>(a, block_size, (unsigned)blocks)
+                                    : launch_multi<PA_BF16>(a, block_size, (unsigned)blocks);
+    if (!ok) return PA_ERR_UNSUPPORTED;
     return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
 }
 

@@ -164,6 +164,59 @@ def test_shared_decode_fully_shared_and_mixed(pa):
         print(dtype, run_and_compare(pa, w, partitions=(SHARED, 0)))
 
 
+# ---------------------------------------------------------------------------
+# several query tokens per sequence (causal), on the matrix cores
+# ---------------------------------------------------------------------------
+def multi_case(pa, dtype, lens, q_lens, H=3, B=16, seed=41):
+    lens, q_lens = np.asarray(lens, dtype=np.int64), np.asarray(q_lens, dtype=np.int64)
+    w = W.independent_sequences("multi", dtype, H, 128, B, lens, seed=seed)
+    v = W.make_values(w)
+    dw = DeviceWorkload(w, v)
+    gpu_cache_ops(pa, dw)
+    kc, vc = oracle_cache_ops(w, v)
+    q_start = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
+    T = int(q_start[-1])
+    rng = np.random.default_rng(seed + 1)
+    q = W.to_storage(rng.standard_normal((T, H, 128)).astype(np.float32), dtype)
+    dq = to_dev(q, dtype)
+    out = torch.full_like(dq, float("nan"))
+    pa.pa_decode_multi(out, dq, dw.k_cache, dw.v_cache, dw.block_tables, dw.context_lens, to_dev(q_start),
+                       int(q_lens.max()), B, float(w.scale), w.max_context_len)
+    torch.cuda.synchronize()
+    ref = oracle.decode_multi(q, kc, vc, w.block_tables, w.context_lens, q_start, w.scale, dtype)
+    got = out_to_f64(out, dtype)
+    assert np.isfinite(got).all()
+    err = float(np.abs(got - ref).max())
+    assert err <= TOL[dtype], "multi %s: max abs err %g" % (dtype, err)
+    return err
+
+
+def test_multi_query_decode(pa):
+    # q_len 1 (= decode), a few, exactly 16, 17 (two query blocks), the whole context, none
+    lens = [1, 2, 15, 16, 17, 33, 64, 100, 257, 700, 700, 1025, 40, 300]
+    q_lens = [1, 2, 15, 16, 17, 5, 64, 1, 16, 40, 3, 31, 0, 300]
+    for dtype in ("f16", "bf16"):
+        print(dtype, multi_case(pa, dtype, lens, q_lens))
+    print("B=32", multi_case(pa, "bf16", lens, q_lens, H=2, B=32))
+    print("B=64", multi_case(pa, "f16", [500, 130, 64], [20, 130, 1], H=2, B=64))
+
+
+def test_multi_query_of_one_equals_decode(pa):
+    w = W.config2(seed=13, num_seqs=12, max_len=600, H=4)
+    v = W.make_values(w)
+    dw = DeviceWorkload(w, v)
+    gpu_cache_ops(pa, dw)
+    a = out_to_f64(gpu_decode(pa, dw, 0), w.dtype)
+    out = torch.empty_like(dw.q)
+    pa.pa_decode_multi(out, dw.q, dw.k_cache, dw.v_cache, dw.block_tables, dw.context_lens,
+                       to_dev(np.arange(w.num_seqs + 1, dtype=np.int32)), 1, w.block_size, float(w.scale),
+                       w.max_context_len)
+    torch.cuda.synchronize()
+    b = out_to_f64(out, w.dtype)
+    # two kernels, two summation orders: equal within one rounding of the output type
+    assert np.abs(a - b).max() <= 2 * TOL[w.dtype]
+
+
 def test_edge_context_lengths(pa):
     # one below / at / one above every boundary the kernels have: block, chunk, partition
     B, PS = 16, 64

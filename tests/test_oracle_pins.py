@@ -279,6 +279,41 @@ def test_rows_subset_matches_full():
     assert np.array_equal(one, full)
 
 
+def test_multi_query_matches_torch_causal_attention():
+    # several new tokens per sequence: against a masked softmax in torch float64 on contiguous K, V
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(18)
+    lens, q_lens, H, D, B = [37, 20, 5, 64], [5, 20, 1, 0], 2, 8, 8
+    _, K, V = rand_seqs(rng, lens, H, D)
+    kc, vc, tables, cl = paged_from_contiguous(K, V, B, 20, rng)
+    q_start = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
+    q = rng.standard_normal((int(q_start[-1]), H, D)).astype(np.float32)
+    scale = np.float32(0.3)
+    out = oracle.decode_multi(q, kc, vc, tables, cl, q_start, scale, "f32")
+    for s, (n, ql) in enumerate(zip(lens, q_lens)):
+        if ql == 0:
+            continue
+        qt = torch.from_numpy(q[q_start[s]:q_start[s + 1]]).double().permute(1, 0, 2)    # [H][ql][D]
+        Kt = torch.from_numpy(K[s]).double().permute(1, 0, 2)
+        Vt = torch.from_numpy(V[s]).double().permute(1, 0, 2)
+        logits = torch.einsum("hqd,hnd->hqn", qt, Kt) * float(scale)
+        pos = torch.arange(n - ql, n).view(1, ql, 1)
+        logits = logits.masked_fill(torch.arange(n).view(1, 1, n) > pos, float("-inf"))
+        ref = torch.einsum("hqn,hnd->hqd", torch.softmax(logits, dim=-1), Vt).permute(1, 0, 2).numpy()
+        assert np.abs(out[q_start[s]:q_start[s + 1]] - ref).max() < 1e-13
+    # one query per sequence is ordinary decode
+    one = np.arange(len(lens) + 1, dtype=np.int32)
+    q1 = rng.standard_normal((len(lens), H, D)).astype(np.float32)
+    assert np.array_equal(oracle.decode_multi(q1, kc, vc, tables, cl, one, scale, "f32"),
+                          oracle.decode(q1, kc, vc, tables, cl, scale, "f32"))
+    # the first of the new tokens of a sequence of exactly q_len tokens sees only itself
+    qs2 = np.array([0, 5], dtype=np.int32)
+    K2, V2 = [K[2]], [V[2]]
+    k2, v2, t2, c2 = paged_from_contiguous(K2, V2, B, 3, np.random.default_rng(1))
+    o2 = oracle.decode_multi(q[:5].copy(), k2, v2, t2, c2, qs2, scale, "f32")
+    assert np.array_equal(o2[0], V[2][0].astype(np.float64))
+
+
 # ---------------------------------------------------------------------------
 # storage decoding: every 16-bit pattern against numpy's own conversions
 # ---------------------------------------------------------------------------
