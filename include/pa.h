@@ -31,10 +31,9 @@
  * above NB*B, duplicate slots, or a copy destination that is also a source or
  * appears twice are undefined behaviour.  pa_debug_validate checks them.
  *
- * Supported: dtype f16/bf16/f32; D*sizeof(elem) in {128, 256, 512} bytes
- * (D = 64, 128, 256 at 2 bytes; D = 32, 64, 128 at 4 bytes); B in
- * {8, 16, 32, 64, 128} with B*D*sizeof(elem) >= 1024; multi-head attention
- * with as many KV heads as query heads (the paper's models).
+ * Supported: dtype f16/bf16/f32; head_dim D in {64, 128}; block_size B in
+ * {8, 16, 32, 64, 128}; multi-head attention with as many KV heads as query
+ * heads (the paper's models).  pa_decode_multi: f16/bf16, D = 128, B >= 16.
  */
 #ifndef PA_H
 #define PA_H

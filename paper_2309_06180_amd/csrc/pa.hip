@@ -1026,6 +1026,7 @@ __global__ __launch_bounds__(256) void reshape_and_cache_kernel(
 
 // ---- copy_blocks -------------------------------------------------------------
 constexpr int kMaxCopyPtrs = 128;   // K and V pointers of up to 64 layers per launch
+constexpr int kMaxPairsPerLaunch = 65535;   // grid.y limit; longer pair lists take several launches
 struct CachePtrs {
     uint4 *p[kMaxCopyPtrs];
 };
@@ -1468,7 +1469,6 @@ pa_status pa_copy_blocks(void *const *k_caches, void *const *v_caches, int32_t n
     if (block_bytes % 16) return PA_ERR_UNSUPPORTED;
     if (num_pairs == 0) return PA_OK;
     if (!k_caches || !v_caches || !src_dst_pairs) return PA_ERR_NULL;
-    if (num_pairs > 65535) return PA_ERR_SHAPE;
     for (int l = 0; l < num_layers; ++l) {
         if (!k_caches[l] || !v_caches[l]) return PA_ERR_NULL;
         if (!aligned16(k_caches[l]) || !aligned16(v_caches[l])) return PA_ERR_ALIGN;
@@ -1483,9 +1483,12 @@ pa_status pa_copy_blocks(void *const *k_caches, void *const *v_caches, int32_t n
             ptrs.p[2 * l] = static_cast<uint4 *>(k_caches[l0 + l]);
             ptrs.p[2 * l + 1] = static_cast<uint4 *>(v_caches[l0 + l]);
         }
-        hipLaunchKernelGGL(copy_blocks_kernel, dim3(slices, (unsigned)num_pairs, (unsigned)(2 * nl)),
-                           dim3(256), 0, static_cast<hipStream_t>(stream), ptrs, src_dst_pairs, frags);
-        if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
+        for (int p0 = 0; p0 < num_pairs; p0 += kMaxPairsPerLaunch) {
+            const int np = num_pairs - p0 < kMaxPairsPerLaunch ? num_pairs - p0 : kMaxPairsPerLaunch;
+            hipLaunchKernelGGL(copy_blocks_kernel, dim3(slices, (unsigned)np, (unsigned)(2 * nl)), dim3(256), 0,
+                               static_cast<hipStream_t>(stream), ptrs, src_dst_pairs + 2 * (int64_t)p0, frags);
+            if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
+        }
     }
     return PA_OK;
 }
@@ -1504,7 +1507,6 @@ pa_status pa_swap_blocks(void *const *src_k_caches, void *const *src_v_caches,
     if (block_bytes % 16) return PA_ERR_UNSUPPORTED;
     if (num_pairs == 0) return PA_OK;
     if (!src_k_caches || !src_v_caches || !dst_k_caches || !dst_v_caches || !src_dst_pairs) return PA_ERR_NULL;
-    if (num_pairs > 65535) return PA_ERR_SHAPE;
     for (int l = 0; l < num_layers; ++l) {
         if (!src_k_caches[l] || !src_v_caches[l] || !dst_k_caches[l] || !dst_v_caches[l]) return PA_ERR_NULL;
         if (!aligned16(src_k_caches[l]) || !aligned16(src_v_caches[l]) || !aligned16(dst_k_caches[l]) ||
@@ -1523,9 +1525,12 @@ pa_status pa_swap_blocks(void *const *src_k_caches, void *const *src_v_caches,
             ptrs.dst[2 * l] = static_cast<uint4 *>(dst_k_caches[l0 + l]);
             ptrs.dst[2 * l + 1] = static_cast<uint4 *>(dst_v_caches[l0 + l]);
         }
-        hipLaunchKernelGGL(swap_blocks_kernel, dim3(slices, (unsigned)num_pairs, (unsigned)(2 * nl)),
-                           dim3(256), 0, static_cast<hipStream_t>(stream), ptrs, src_dst_pairs, frags);
-        if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
+        for (int p0 = 0; p0 < num_pairs; p0 += kMaxPairsPerLaunch) {
+            const int np = num_pairs - p0 < kMaxPairsPerLaunch ? num_pairs - p0 : kMaxPairsPerLaunch;
+            hipLaunchKernelGGL(swap_blocks_kernel, dim3(slices, (unsigned)np, (unsigned)(2 * nl)), dim3(256), 0,
+                               static_cast<hipStream_t>(stream), ptrs, src_dst_pairs + 2 * (int64_t)p0, frags);
+            if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
+        }
     }
     return PA_OK;
 }

@@ -402,3 +402,46 @@ def test_workspace_and_argument_errors_on_device(pa):
         pa.pa_decode(out, dw.q, dw.k_cache, dw.v_cache, dw.block_tables, dw.context_lens, w.block_size,
                      float(w.scale), w.max_context_len, 24, small)       # not a multiple of the block size
     assert e.value.code == 2
+
+
+def test_side_stream_and_graph_replay(pa):
+    # the calls enqueue on torch's current stream; a captured step (cache write + decode) replays
+    # with new inputs written in place, and every replay matches the eager result
+    w = W.config2(seed=17, num_seqs=16, max_len=500, H=4)
+    v = W.make_values(w)
+    dw = DeviceWorkload(w, v)
+    out = torch.empty_like(dw.q)
+    k_new, v_new = dw.k_new.clone(), dw.v_new.clone()
+
+    def step():
+        pa.pa_reshape_and_cache(k_new, v_new, dw.k_cache, dw.v_cache, dw.write_slots)
+        pa.pa_decode(out, dw.q, dw.k_cache, dw.v_cache, dw.block_tables, dw.context_lens, w.block_size,
+                     float(w.scale), w.max_context_len, 0, None)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    side.synchronize()
+    eager0 = out.clone()
+    kc, vc = oracle_cache_ops(w, v)
+    ref = oracle.decode(v.q, kc, vc, w.block_tables, w.context_lens, w.scale, w.dtype)
+    assert np.abs(out_to_f64(eager0, w.dtype) - ref).max() <= TOL[w.dtype]
+
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    for it in range(3):
+        k_new.copy_(torch.randn(k_new.shape, device="cuda", generator=gen).to(k_new.dtype))
+        v_new.copy_(torch.randn(v_new.shape, device="cuda", generator=gen).to(v_new.dtype))
+        dw.q.copy_(torch.randn(dw.q.shape, device="cuda", generator=gen).to(dw.q.dtype))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        replayed = out.clone()
+        step()                                        # the program's own eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(replayed, out), "replay %d differs from eager" % it
+        assert not torch.equal(replayed, eager0)
