@@ -1,0 +1,396 @@
+// libpa paged decode: the VALU decode kernel (one pass, fixed partitions, suffix, shared prefix) and the merge kernel.
+#ifndef PA_PA_DECODE_HPP
+#define PA_PA_DECODE_HPP
+
+#include "pa_common.hpp"
+
+namespace {
+
+// ---- decode ----------------------------------------------------------------
+// One workgroup of W wavefronts serves one work item: a (sequence, head) over
+// its whole context, over one fixed-size partition of it, or over the suffix
+// that follows a shared prefix; or a (group of sequences, head) over the
+// prefix of physical blocks the group has in common.
+//
+// Lane roles: a token row is LPT = D*E/16 lanes wide, so one 1 KiB wavefront
+// load covers TPL = 64/LPT consecutive tokens; lane = g*LPT + c holds
+// dimensions [c*EPL, (c+1)*EPL) of token (base + g).  Work advances in chunks
+// of LPC loads (CT = LPC*TPL tokens, at most one block); wave w takes chunks
+// w, w+W, ...; U chunks (2*U*LPC KiB of K and V) are requested together
+// before any of them is used.
+//
+// Each group g of lanes runs its own online softmax over the tokens it sees
+// (running maximum m, sum l, weighted V sum acc, all fp32, exponents in base
+// 2 with log2(e) folded into the scale).  Groups and waves are merged once at
+// the end with the log-sum-exp rule, so the inner loop has no cross-group
+// traffic.  Summation order depends only on logical token positions, so the
+// result does not change with the physical placement of blocks.
+//
+// In the shared-prefix mode the workgroup holds the queries of up to G
+// sequences and applies every K/V fragment it loads to all of them, so blocks
+// that several sequences map (parallel sampling, beam search: Sec. 4.4) are
+// read from memory once per group instead of once per sequence.
+enum DecodeMode {
+    MODE_SINGLE = 0,   // whole context, writes the output row
+    MODE_PART = 1,     // tokens [part*PS, (part+1)*PS), writes partial `part` of max_parts
+    MODE_SUFFIX = 2,   // tokens [range_begin[s], n), writes partial 1 of 2
+    MODE_PREFIX = 3    // tokens [0, prefix) of a group, writes partial 0 of 2 for every member
+};
+
+struct DecodeParams {
+    void *out;
+    const void *q;
+    const char *k_cache, *v_cache;
+    const int32_t *block_tables;
+    const int32_t *context_lens;
+    const int32_t *ginfo;   // group table built by find_groups_kernel (shared-prefix path)
+    const int32_t *q_start; // multi-query path: first query row of every sequence, [S+1]
+    float *ws_acc, *ws_ml;
+    int32_t max_blocks, S, H;
+    int32_t partition_size, max_parts;
+    int32_t prefix_blocks;   // fused shared-prefix launch: workgroups [0, prefix_blocks) are prefix items
+    int32_t q_blocks;        // multi-query path: blocks of 16 queries per sequence in the grid
+    float scale_log2;
+};
+
+// Layout of the group table, three arrays of S entries: range_begin[s] (tokens
+// of s covered by its group's shared prefix), group_size[s] (members of the
+// group that starts at sequence s, 0 if none starts there) and
+// group_prefix_tokens[s] (tokens all members of that group have in common).
+__device__ __host__ __forceinline__ int ginfo_range_begin(int S, int s) { (void)S; return s; }
+__device__ __host__ __forceinline__ int ginfo_group_size(int S, int s) { return S + s; }
+__device__ __host__ __forceinline__ int ginfo_group_prefix(int S, int s) { return 2 * S + s; }
+__device__ __host__ __forceinline__ int ginfo_adj(int S, int s) { return 3 * S + s; }
+// compact list of the first sequences of groups with two or more members, and its length
+__device__ __host__ __forceinline__ int ginfo_shared_list(int S, int i) { return 4 * S + i; }
+__device__ __host__ __forceinline__ int ginfo_shared_count(int S) { return 5 * S; }
+__device__ __host__ __forceinline__ size_t ginfo_words(int S) { return 5 * (size_t)S + 4; }
+
+// A sixteen-wave workgroup is kept alone on its compute unit (at most 7 waves
+// per SIMD, so a second one does not fit): measured on batches of mixed
+// lengths, two resident workgroups each run at half speed and stretch the end
+// of the launch by more than their overlap gains.
+#define PA_OCC_ATTR __attribute__((amdgpu_waves_per_eu(W == 16 ? 4 : 1, W == 16 ? 7 : 8)))
+#define PA_OCC_ATTR_FUSED __attribute__((amdgpu_waves_per_eu(WS == 16 ? 4 : 1, WS == 16 ? 7 : 8)))
+template <int DT, int D, int B, int W, int U, int MODE, int G>
+__device__ __forceinline__ void decode_body(const DecodeParams &P, const int block_index)
+{
+    using Tr = Traits<DT>;
+    constexpr int E = Tr::E, EPL = Tr::EPL;
+    constexpr int ROW_BYTES = D * E;
+    constexpr int LPT = ROW_BYTES / 16;
+    constexpr int TPL = kWave / LPT;
+    constexpr int LPC = (B / TPL) < 4 ? (B / TPL) : 4;
+    constexpr int CT = LPC * TPL;
+    constexpr int64_t TILE_BYTES = (int64_t)B * ROW_BYTES;
+    static_assert(LPT >= 8 && LPT <= 32 && B % TPL == 0 && B % CT == 0 && LPC >= 1, "shape");
+    static_assert(G == 1 || MODE == MODE_PREFIX, "several queries only in the shared-prefix mode");
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int g = lane / LPT;
+    const int c = lane % LPT;
+    const uint32_t lane16 = (uint32_t)lane * 16u;
+    const int H = P.H;
+
+    int item = block_index;
+    const int h = item % H;
+    item /= H;
+
+    // s: the sequence whose block table is walked; members: query slots in use
+    int s, part = 0, parts_stride = 1, t_begin = 0, t_end, members = 1;
+    if (MODE == MODE_PREFIX) {
+        if (item >= P.ginfo[ginfo_shared_count(P.S)]) return;
+        s = P.ginfo[ginfo_shared_list(P.S, item)];   // a group is named by its first sequence
+        members = P.ginfo[ginfo_group_size(P.S, s)];
+        t_end = P.ginfo[ginfo_group_prefix(P.S, s)];
+        parts_stride = 2;
+        if (members < 2) return;
+    } else if (MODE == MODE_SUFFIX) {
+        s = item;
+        t_begin = P.ginfo[ginfo_range_begin(P.S, s)];
+        t_end = P.context_lens[s];
+        part = 1;
+        parts_stride = 2;
+    } else if (MODE == MODE_PART) {
+        part = item % P.max_parts;
+        s = item / P.max_parts;
+        parts_stride = P.max_parts;
+        const int n = P.context_lens[s];
+        t_begin = part * P.partition_size;
+        t_end = t_begin + P.partition_size < n ? t_begin + P.partition_size : n;
+    } else {
+        s = item;
+        t_end = P.context_lens[s];
+    }
+    if (t_begin >= t_end) {
+        if (MODE == MODE_SINGLE && w == 0 && g == 0) {
+            // empty context: zero row
+            reinterpret_cast<uint4 *>(P.out)[((int64_t)s * H + h) * LPT + c] = make_uint4(0, 0, 0, 0);
+        }
+        return;
+    }
+
+    // members of a group are consecutive sequences s, s+1, ...
+    uint4 qf[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        const int sj = j < members ? s + j : s;
+        qf[j] = reinterpret_cast<const uint4 *>(P.q)[((int64_t)sj * H + h) * LPT + c];
+    }
+    const int32_t *__restrict__ table = P.block_tables + (int64_t)s * P.max_blocks;
+    const int nchunks = (t_end - t_begin + CT - 1) / CT;
+
+    float m[G], l[G], acc[G][EPL];
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        m[j] = kNegBig;
+        l[j] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[j][e] = 0.f;
+    }
+
+    struct Chunk {
+        uint4 k[LPC], v[LPC];
+    };
+
+    auto block_of = [&](int ci) -> int {
+        // ci is wave-uniform: this is a scalar load
+        return table[(t_begin + ci * CT) / B];
+    };
+    auto issue = [&](Chunk &ck, int ci, int pb) {
+        const int t0 = t_begin + ci * CT;
+        const int64_t off = ((int64_t)pb * H + h) * TILE_BYTES + (int64_t)(t0 % B) * ROW_BYTES;
+        const char *kp = P.k_cache + off + lane16;
+        const char *vp = P.v_cache + off + lane16;
+#pragma unroll
+        for (int i = 0; i < LPC; ++i) ck.k[i] = load16_stream(kp + i * 1024);
+#pragma unroll
+        for (int i = 0; i < LPC; ++i) ck.v[i] = load16_stream(vp + i * 1024);
+    };
+    // MASK is set only for a chunk that may reach past t_end (the last one)
+    auto consume = [&](Chunk &ck, int ci, auto mask_tag) {
+        constexpr bool MASK = decltype(mask_tag)::value;
+        const int t0 = t_begin + ci * CT;
+        if (MASK) {
+            // slots at or past t_end hold no token and may contain anything, NaN
+            // included - select them away, never multiply
+#pragma unroll
+            for (int i = 0; i < LPC; ++i) {
+                const bool dead = t0 + i * TPL + g >= t_end;
+                ck.v[i].x = dead ? 0u : ck.v[i].x;
+                ck.v[i].y = dead ? 0u : ck.v[i].y;
+                ck.v[i].z = dead ? 0u : ck.v[i].z;
+                ck.v[i].w = dead ? 0u : ck.v[i].w;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            if (G > 1 && j >= members) break;
+            float x[LPC];
+#pragma unroll
+            for (int i = 0; i < LPC; ++i) x[i] = group_sum<LPT>(Tr::dot(ck.k[i], qf[j], 0.f)) * P.scale_log2;
+            if (MASK) {
+#pragma unroll
+                for (int i = 0; i < LPC; ++i) x[i] = (t0 + i * TPL + g >= t_end) ? -INFINITY : x[i];
+            }
+            float m_new = m[j];
+#pragma unroll
+            for (int i = 0; i < LPC; ++i) m_new = fmaxf(m_new, x[i]);
+            const float alpha = __builtin_amdgcn_exp2f(m[j] - m_new);
+            float p[LPC], psum = 0.f;
+#pragma unroll
+            for (int i = 0; i < LPC; ++i) {
+                p[i] = __builtin_amdgcn_exp2f(x[i] - m_new);
+                psum += p[i];
+            }
+            l[j] = l[j] * alpha + psum;
+            m[j] = m_new;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[j][e] *= alpha;
+#pragma unroll
+            for (int i = 0; i < LPC; ++i) {
+                Tr::axpy(acc[j], p[i], ck.v[i]);
+                // bf16 widening is two VALU ops per pair; without a fence the
+                // scheduler widens every fragment first and doubles the live registers
+                if (Tr::FENCE_AXPY) __builtin_amdgcn_sched_barrier(0);
+            }
+            // one member at a time: interleaving their arithmetic multiplies the live registers
+            if (G > 1) __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    const std::false_type full{};
+    const std::true_type masked{};
+
+    // Steady state: U chunks per trip, all loads issued up front, then consumed
+    // in order, in one straight-line block (nothing loaded is carried across the
+    // back edge, so the compiler waits exactly for the fragment it needs next).
+    // Chunks before the last one of the range are full; the remainder loop takes
+    // one chunk at a time with masking.  Latency is hidden by the other waves
+    // resident on the SIMD.
+    {
+        int ci = w;
+        for (; ci + (U - 1) * W <= nchunks - 2; ci += U * W) {
+            Chunk ck[U];
+            int pb[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) pb[u] = block_of(ci + u * W);
+#pragma unroll
+            for (int u = 0; u < U; ++u) issue(ck[u], ci + u * W, pb[u]);
+#pragma unroll
+            for (int u = 0; u < U; ++u) consume(ck[u], ci + u * W, full);
+        }
+        for (; ci < nchunks; ci += W) {
+            Chunk ck;
+            issue(ck, ci, block_of(ci));
+            consume(ck, ci, masked);
+        }
+    }
+
+    // merge the TPL token groups of this wave (lanes with equal c)
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        float M = m[j];
+#pragma unroll
+        for (int d = LPT; d < kWave; d <<= 1) M = fmaxf(M, __shfl_xor(M, d));
+        const float f = __builtin_amdgcn_exp2f(m[j] - M);
+        l[j] *= f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[j][e] *= f;
+#pragma unroll
+        for (int d = LPT; d < kWave; d <<= 1) {
+            l[j] += __shfl_xor(l[j], d);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[j][e] += __shfl_xor(acc[j][e], d);
+        }
+        m[j] = M;
+    }
+
+    // merge the W waves of the workgroup through LDS
+    if (W > 1) {
+        __shared__ float sm_acc[W][G][D];
+        __shared__ float sm_m[W][G], sm_l[W][G];
+        if (g == 0) {
+#pragma unroll
+            for (int j = 0; j < G; ++j) {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) sm_acc[w][j][c * EPL + e] = acc[j][e];
+                if (c == 0) {
+                    sm_m[w][j] = m[j];
+                    sm_l[w][j] = l[j];
+                }
+            }
+        }
+        __syncthreads();
+        if (w != 0) return;
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            float M = sm_m[0][j];
+#pragma unroll
+            for (int i = 1; i < W; ++i) M = fmaxf(M, sm_m[i][j]);
+            l[j] = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[j][e] = 0.f;
+            // (not fully unrolled: sixteen waves' worth of LDS reads hoisted at once would spill)
+#pragma unroll 2
+            for (int i = 0; i < W; ++i) {
+                const float f = __builtin_amdgcn_exp2f(sm_m[i][j] - M);
+                l[j] = __builtin_fmaf(sm_l[i][j], f, l[j]);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e)
+                    acc[j][e] = __builtin_fmaf(sm_acc[i][j][c * EPL + e], f, acc[j][e]);
+            }
+            m[j] = M;
+        }
+    }
+    if (g != 0) return;
+
+    if (MODE == MODE_SINGLE) {
+        const float inv = 1.0f / l[0];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[0][e] *= inv;
+        reinterpret_cast<uint4 *>(P.out)[((int64_t)s * H + h) * LPT + c] = Tr::pack(acc[0]);
+    } else {
+        // unnormalised partials: the reduce kernel divides once
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            if (j >= members) break;
+            const int64_t slot = ((int64_t)(s + j) * H + h) * parts_stride + part;
+            float *dst = P.ws_acc + slot * D + c * EPL;
+#pragma unroll
+            for (int e = 0; e < EPL; e += 4)
+                *reinterpret_cast<float4 *>(dst + e) =
+                    make_float4(acc[j][e], acc[j][e + 1], acc[j][e + 2], acc[j][e + 3]);
+            if (c == 0) *reinterpret_cast<float2 *>(P.ws_ml + slot * 2) = make_float2(m[j], l[j]);
+        }
+    }
+}
+
+template <int DT, int D, int B, int W, int U, int MODE, int G>
+__global__ __launch_bounds__(W *kWave) PA_OCC_ATTR void pa_decode_kernel(const DecodeParams P)
+{
+    decode_body<DT, D, B, W, U, MODE, G>(P, (int)blockIdx.x);
+}
+
+// Merge of partials: out = sum_p 2^(m_p-M) a_p / sum_p 2^(m_p-M) l_p with a_p the
+// unnormalised partial sums.  One wavefront per (sequence, head); lane c
+// handles the same 16-byte output fragment as in the decode kernel.  With
+// fixed partitions the first ceil(n/PS) partials exist; on the shared-prefix
+// path partial 0 (prefix) exists when range_begin[s] > 0 and partial 1
+// (suffix) when range_begin[s] < n.
+template <int DT, int D, bool SHARED>
+__global__ __launch_bounds__(kWave) void pa_reduce_kernel(const DecodeParams P)
+{
+    using Tr = Traits<DT>;
+    constexpr int EPL = Tr::EPL;
+    constexpr int LPT = D * Tr::E / 16;
+    const int c = threadIdx.x;
+    if (c >= LPT) return;
+    const int H = P.H;
+    const int h = blockIdx.x % H;
+    const int s = blockIdx.x / H;
+    const int n = P.context_lens[s];
+    int first = 0, last, stride;
+    if (SHARED) {
+        const int rb = P.ginfo[ginfo_range_begin(P.S, s)];
+        stride = 2;
+        first = rb > 0 ? 0 : 1;
+        last = n > rb ? 2 : 1;
+    } else {
+        stride = P.max_parts;
+        last = (n + P.partition_size - 1) / P.partition_size;
+        if (last > stride) last = stride;
+    }
+    const int64_t base = ((int64_t)s * H + h) * stride;
+    float acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+    if (n > 0 && first < last) {
+        float M = kNegBig;
+        for (int p = first; p < last; ++p) M = fmaxf(M, P.ws_ml[(base + p) * 2]);
+        float l = 0.f;
+        for (int p = first; p < last; ++p) {
+            const float2 ml = *reinterpret_cast<const float2 *>(P.ws_ml + (base + p) * 2);
+            const float f = __builtin_amdgcn_exp2f(ml.x - M);
+            l = __builtin_fmaf(ml.y, f, l);
+            const float *src = P.ws_acc + (base + p) * D + c * EPL;
+#pragma unroll
+            for (int e = 0; e < EPL; e += 4) {
+                const float4 a = *reinterpret_cast<const float4 *>(src + e);
+                acc[e] = __builtin_fmaf(a.x, f, acc[e]);
+                acc[e + 1] = __builtin_fmaf(a.y, f, acc[e + 1]);
+                acc[e + 2] = __builtin_fmaf(a.z, f, acc[e + 2]);
+                acc[e + 3] = __builtin_fmaf(a.w, f, acc[e + 3]);
+            }
+        }
+        const float inv = 1.0f / l;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] *= inv;
+    }
+    reinterpret_cast<uint4 *>(P.out)[((int64_t)s * H + h) * LPT + c] = Tr::pack(acc);
+}
+
+
+} // namespace
+
+#endif
