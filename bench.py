@@ -49,6 +49,10 @@ def parse():
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--block-size-sweep", action="store_true",
                     help="instead of the step benchmark: pa_decode at the OPT-13B shape for B = 8..128")
+    ap.add_argument("--cfg5-full-step", action="store_true",
+                    help="instead of the step benchmark: the whole 40-layer beam-search step of config 5 "
+                         "(~142 GB of cache filled on the device): copy-on-write for all layers, then per "
+                         "layer cache write + decode")
     ap.add_argument("--multi-query", action="store_true",
                     help="instead of the step benchmark: pa_decode_multi at the OPT-13B shape for several q_len")
     ap.add_argument("--cache-ops", action="store_true",
@@ -109,6 +113,52 @@ def block_size_sweep(pa, W, np, torch, dev):
         del kc, vc
     print(json.dumps({"metric": "pa_decode_block_size_sweep", "workload": "OPT-13B shape, 64 seq, ctx U{1..2048}, fp16",
                       "rows": rows}))
+
+
+def cfg5_full_step(pa, W, np, torch, dev, steps):
+    """Config 5 at full size: 40 layers x 40 heads x 128, B = 32, bf16, 128 sequences in beam groups of 6,
+    one beam-search step per iteration: pa_copy_blocks over all layers, then per layer
+    pa_reshape_and_cache (T = 128) and decode.  Caches are filled on the device (timing only)."""
+    L = 40
+    w = W.config5()
+    S, H, D, B, NB = w.num_seqs, w.num_heads, w.head_dim, w.block_size, w.num_blocks
+    ks = [torch.randn((NB, H, B, D), dtype=torch.bfloat16, device=dev) for _ in range(L)]
+    vs = [torch.randn((NB, H, B, D), dtype=torch.bfloat16, device=dev) for _ in range(L)]
+    q = torch.randn((S, H, D), dtype=torch.bfloat16, device=dev)
+    out = torch.empty_like(q)
+    k_new = torch.randn((S, H, D), dtype=torch.bfloat16, device=dev)
+    v_new = torch.randn((S, H, D), dtype=torch.bfloat16, device=dev)
+    bt, cl = torch.from_numpy(w.block_tables).to(dev), torch.from_numpy(w.context_lens).to(dev)
+    slots, pairs = torch.from_numpy(w.write_slots).to(dev), torch.from_numpy(w.copy_pairs).to(dev)
+    mcl = w.max_context_len
+    ws = torch.empty(max(pa.pa_decode_shared_workspace_bytes(S, H, D),
+                         pa.pa_decode_workspace_bytes(S, H, D, B, mcl, pa.PA_PARTITION_AUTO), 16),
+                     dtype=torch.uint8, device=dev)
+    res = {"metric": "cfg5_full_step", "layers": L, "num_seqs": S, "pool_blocks": NB,
+           "cache_GB": 2 * L * NB * H * B * D * 2 / 1e9, "copy_pairs": int(len(w.copy_pairs)),
+           "kv_GB_logical_per_step": L * w.kv_bytes_logical() / 1e9,
+           "kv_GB_unique_per_step": L * w.kv_bytes_unique() / 1e9}
+    for name in ("plain", "shared"):
+        def step():
+            pa.pa_copy_blocks(ks, vs, pairs)
+            for l in range(L):
+                pa.pa_reshape_and_cache(k_new, v_new, ks[l], vs[l], slots)
+                if name == "shared":
+                    pa.pa_decode_shared(out, q, ks[l], vs[l], bt, cl, B, float(w.scale), mcl, ws)
+                else:
+                    pa.pa_decode(out, q, ks[l], vs[l], bt, cl, B, float(w.scale), mcl, pa.PA_PARTITION_AUTO, ws)
+        for _ in range(2):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        res[name] = {"ms_per_step": ms, "query_tokens_per_s": S / ms * 1e3,
+                     "logical_kv_GBps": L * w.kv_bytes_logical() / ms / 1e6,
+                     "unique_kv_frac_of_peak": L * w.kv_bytes_unique() / ms / 1e6 / HBM_PEAK_GBPS}
+    print(json.dumps(res))
 
 
 def multi_query(pa, W, np, torch, dev):
@@ -210,6 +260,8 @@ def main():
         return cache_ops(pa, np, torch, dev)
     if args.multi_query:
         return multi_query(pa, W, np, torch, dev)
+    if args.cfg5_full_step:
+        return cfg5_full_step(pa, W, np, torch, dev, min(args.steps, 10))
 
     make = {"cfg1": W.config1, "cfg2": W.config2, "cfg3": W.config3, "cfg4": W.config4,
             "cfg5": W.config5}[args.workload]
