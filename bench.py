@@ -390,7 +390,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic",
+        "dtype": w.dtype, "accumulate": "f32", "data": "synthetic",
         "config": {"workload": w.name, "num_seqs": S, "num_heads": H, "head_dim": D, "block_size": B,
                    "num_blocks": w.num_blocks, "context_tokens": int(w.context_lens.sum()),
                    "max_context_len": mcl, "partition_size": ps, "seed": w.seed, "decode": args.decode, "launch": args.launch,
