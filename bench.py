@@ -131,7 +131,7 @@ def cfg5_full_step(pa, W, np, torch, dev, steps):
     bt, cl = torch.from_numpy(w.block_tables).to(dev), torch.from_numpy(w.context_lens).to(dev)
     slots, pairs = torch.from_numpy(w.write_slots).to(dev), torch.from_numpy(w.copy_pairs).to(dev)
     mcl = w.max_context_len
-    ws = torch.empty(max(pa.pa_decode_shared_workspace_bytes(S, H, D),
+    ws = torch.empty(max(pa.pa_decode_shared_workspace_bytes(S, H, D, w.max_blocks_per_seq),
                          pa.pa_decode_workspace_bytes(S, H, D, B, mcl, pa.PA_PARTITION_AUTO), 16),
                      dtype=torch.uint8, device=dev)
     res = {"metric": "cfg5_full_step", "layers": L, "num_seqs": S, "pool_blocks": NB,
@@ -299,7 +299,7 @@ def main():
     mcl = w.max_context_len
     ps = pa.PA_PARTITION_AUTO if args.partition is None else args.partition
     shared = args.decode == "shared"
-    ws_bytes = pa.pa_decode_shared_workspace_bytes(S, H, D) if shared else \
+    ws_bytes = pa.pa_decode_shared_workspace_bytes(S, H, D, w.max_blocks_per_seq) if shared else \
         pa.pa_decode_workspace_bytes(S, H, D, B, mcl, ps)
     d_ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
 

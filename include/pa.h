@@ -111,19 +111,21 @@ size_t pa_decode_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t he
  * pa_decode_shared - pa_decode for batches whose sequences share physical
  * blocks (Sec. 4.4: samples of one prompt and beams of one search map their
  * common logical blocks to the same physical blocks).  Same arguments, same
- * result as pa_decode; the difference is traffic.  The library compares the
- * block tables of consecutive sequences on the device, groups up to 8
- * neighbours (4 for fp32 or head_dim 64) whose tables start with the same
- * full blocks, reads that common prefix once per group while applying it to
- * every member's query (on the matrix cores for 2-byte types at head_dim 128),
- * reads each sequence's remaining tokens separately, and merges the two
- * partial results per sequence with the log-sum-exp rule (the split-context
- * merge).  Sequences that share nothing are handled as groups of one.
+ * result as pa_decode; the difference is traffic.  On the device, the library
+ * compares the block tables of consecutive sequences, groups up to 8
+ * neighbours that have leading blocks in common, lists every distinct
+ * physical block of a group once with the set of members that map it, and
+ * runs each group through a kernel that applies every K/V tile it loads to
+ * all members mapping it (on the matrix cores) and writes the members'
+ * finished output rows.  Sequences that share nothing go through the
+ * ordinary one-pass kernel in the same launch.
  *
  * Callers should place sequences that were forked from one another next to
- * each other in the batch; any order is correct, only adjacent sharing is
- * exploited.  `workspace` must hold pa_decode_shared_workspace_bytes(...)
- * bytes.  Three or four kernels are enqueued on `stream`.
+ * each other in the batch; any order is correct, only sharing between
+ * neighbours is exploited.  `workspace` must hold
+ * pa_decode_shared_workspace_bytes(...) bytes.  Three kernels are enqueued on
+ * `stream`.  2-byte types at head_dim 128 with block_size >= 16; other shapes
+ * run pa_decode's one-pass kernel (same result, no saving).
  */
 pa_status pa_decode_shared(void *out, const void *q, const void *k_cache, const void *v_cache,
                            const int32_t *block_tables, int32_t max_blocks_per_seq,
@@ -132,7 +134,8 @@ pa_status pa_decode_shared(void *out, const void *q, const void *k_cache, const 
                            pa_dtype dtype, float scale, int32_t max_context_len, void *workspace,
                            size_t workspace_bytes, void *stream);
 
-size_t pa_decode_shared_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t head_dim);
+size_t pa_decode_shared_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t head_dim,
+                                        int32_t max_blocks_per_seq);
 
 /*
  * pa_decode_multi - several query tokens per sequence over the paged cache:

@@ -51,7 +51,7 @@ def load_library() -> ctypes.CDLL:
     lib.pa_decode_shared.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i64, ctypes.c_int,
                                      ctypes.c_float, i32, vp, sz, vp]
     lib.pa_decode_shared_workspace_bytes.restype = sz
-    lib.pa_decode_shared_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.pa_decode_shared_workspace_bytes.argtypes = [i32, i32, i32, i32]
     lib.pa_decode_multi.restype = ctypes.c_int
     lib.pa_decode_multi.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i64, ctypes.c_int,
                                     ctypes.c_float, i32, vp]
@@ -124,8 +124,10 @@ def pa_decode(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache
         float(scale), int(max_context_len), int(partition_size), ws_ptr, ws_bytes, _stream()))
 
 
-def pa_decode_shared_workspace_bytes(num_seqs: int, num_heads: int, head_dim: int) -> int:
-    return int(load_library().pa_decode_shared_workspace_bytes(num_seqs, num_heads, head_dim))
+def pa_decode_shared_workspace_bytes(num_seqs: int, num_heads: int, head_dim: int,
+                                     max_blocks_per_seq: int) -> int:
+    return int(load_library().pa_decode_shared_workspace_bytes(num_seqs, num_heads, head_dim,
+                                                               max_blocks_per_seq))
 
 
 def pa_decode_shared(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,

@@ -63,12 +63,39 @@ struct DecodeArgs {
     hipStream_t stream;
 };
 
-template <int DT, int D, int B, int W, int MODE, int G = 1>
+template <int DT, int D, int B, int W, int MODE>
 void launch_decode_kernel(const DecodeArgs &a, unsigned items)
 {
-    hipLaunchKernelGGL((pa_decode_kernel<DT, D, B, W, (G > 1 ? 1 : kChunksPerTrip), MODE, G>),
-                       dim3(items * (unsigned)a.p.H),
+    hipLaunchKernelGGL((pa_decode_kernel<DT, D, B, W, kChunksPerTrip, MODE>), dim3(items * (unsigned)a.p.H),
                        dim3(W * kWave), 0, a.stream, a.p);
+}
+
+enum PlanMode { PLAN_SINGLE = 0, PLAN_PART = 1, PLAN_SHARED = 2 };
+
+// pa_decode_shared: group discovery, tile lists, then one launch with the shared groups on the
+// matrix cores and everything else on the ordinary one-pass kernel
+template <int DT, int D, int B>
+void launch_shared(const DecodeArgs &a)
+{
+    if constexpr (DT != PA_F32 && D == 128 && B % 16 == 0) {
+        const unsigned S = (unsigned)a.p.S;
+        hipLaunchKernelGGL(find_groups_kernel, dim3(1), dim3(kGroupThreads), 0, a.stream, a.p.block_tables,
+                           a.p.max_blocks, a.p.context_lens, a.p.S, B, kGroupMaxMfma,
+                           const_cast<int32_t *>(a.p.ginfo));
+        // a shared group has two or more members: at most S/2 groups
+        const unsigned max_groups = (S + 1) / 2;
+        hipLaunchKernelGGL(build_tiles_kernel, dim3((max_groups + kTileWaves - 1) / kTileWaves),
+                           dim3(kTileWaves * kWave), 0, a.stream, a.p.block_tables, a.p.max_blocks,
+                           a.p.context_lens, a.p.S, B, const_cast<int32_t *>(a.p.ginfo),
+                           const_cast<int2 *>(a.p.tiles));
+        DecodeArgs f = a;
+        f.p.group_blocks = (int32_t)(max_groups * (unsigned)a.p.H);
+        const unsigned blocks = (unsigned)f.p.group_blocks + S * (unsigned)a.p.H;
+        if (a.waves >= 8)
+            hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 8>), dim3(blocks), dim3(8 * kWave), 0, a.stream, f.p);
+        else
+            hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 4>), dim3(blocks), dim3(4 * kWave), 0, a.stream, f.p);
+    }
 }
 
 template <int DT, int D, int B>
@@ -76,39 +103,14 @@ void dispatch_mode(const DecodeArgs &a, int mode)
 {
     const unsigned S = (unsigned)a.p.S;
     const unsigned rows = S * (unsigned)a.p.H;
-    if (mode == MODE_PART) {
+    if (mode == PLAN_PART) {
         if (a.waves >= 8)
             launch_decode_kernel<DT, D, B, 8, MODE_PART>(a, S * (unsigned)a.p.max_parts);
         else
             launch_decode_kernel<DT, D, B, 4, MODE_PART>(a, S * (unsigned)a.p.max_parts);
-        hipLaunchKernelGGL((pa_reduce_kernel<DT, D, false>), dim3(rows), dim3(kWave), 0, a.stream, a.p);
-    } else if (mode == MODE_PREFIX) {
-        // shared-prefix path: group table, prefixes once per group, private suffixes, merge
-        constexpr bool kMfma = DT != PA_F32 && D == 128 && B % 16 == 0;
-        hipLaunchKernelGGL(find_groups_kernel, dim3(1), dim3(kGroupThreads), 0, a.stream, a.p.block_tables,
-                           a.p.max_blocks, a.p.context_lens, a.p.S, B, kMfma ? kGroupMaxMfma : kGroupMax,
-                           const_cast<int32_t *>(a.p.ginfo));
-        if constexpr (kMfma) {
-            // a shared group has two or more members: at most S/2 groups
-            DecodeArgs f = a;
-            f.p.prefix_blocks = (int32_t)(((S + 1) / 2) * (unsigned)a.p.H);
-            const unsigned blocks = (unsigned)f.p.prefix_blocks + rows;
-            // eight waves per workgroup: two workgroups share a compute unit, so a short prefix
-            // item's load latency is covered by a streaming suffix item (measured better than sixteen)
-            if (a.waves >= 8)
-                hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 8, 8>), dim3(blocks), dim3(8 * kWave), 0, a.stream, f.p);
-            else
-                hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 4, 4>), dim3(blocks), dim3(4 * kWave), 0, a.stream, f.p);
-        } else {
-            launch_decode_kernel<DT, D, B, 8, MODE_PREFIX, kGroupMax>(a, S);
-            if (a.waves >= 16)
-                launch_decode_kernel<DT, D, B, 16, MODE_SUFFIX>(a, S);
-            else if (a.waves >= 8)
-                launch_decode_kernel<DT, D, B, 8, MODE_SUFFIX>(a, S);
-            else
-                launch_decode_kernel<DT, D, B, 4, MODE_SUFFIX>(a, S);
-        }
-        hipLaunchKernelGGL((pa_reduce_kernel<DT, D, true>), dim3(rows), dim3(kWave), 0, a.stream, a.p);
+        hipLaunchKernelGGL((pa_reduce_kernel<DT, D>), dim3(rows), dim3(kWave), 0, a.stream, a.p);
+    } else if (mode == PLAN_SHARED) {
+        launch_shared<DT, D, B>(a);
     } else {
         switch (a.waves) {
         case 2: launch_decode_kernel<DT, D, B, 2, MODE_SINGLE>(a, S); break;
@@ -228,6 +230,14 @@ void fill_common(DecodeArgs &a, void *out, const void *q, const void *k_cache, c
     a.stream = static_cast<hipStream_t>(stream);
 }
 
+bool shared_on_matrix_cores(pa_dtype dtype, int32_t head_dim, int32_t block_size, int32_t max_blocks)
+{
+    // tile-list entries keep the logical block index in 15 bits
+    return dtype != PA_F32 && head_dim == 128 && block_size % 16 == 0 && max_blocks <= 32768;
+}
+
+size_t ginfo_bytes(int32_t S) { return (ginfo_words(S) * sizeof(int32_t) + 15) & ~(size_t)15; }
+
 } // namespace
 
 extern "C" {
@@ -300,16 +310,16 @@ pa_status pa_decode(void *out, const void *q, const void *k_cache, const void *v
         a.p.ws_acc = static_cast<float *>(workspace);
         a.p.ws_ml = a.p.ws_acc + (size_t)num_seqs * num_heads * a.p.max_parts * head_dim;
     }
-    if (!dispatch_decode(a, dtype, head_dim, block_size, partition_size > 0 ? MODE_PART : MODE_SINGLE))
+    if (!dispatch_decode(a, dtype, head_dim, block_size, partition_size > 0 ? PLAN_PART : PLAN_SINGLE))
         return PA_ERR_UNSUPPORTED;
     return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
 }
 
-size_t pa_decode_shared_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t head_dim)
+size_t pa_decode_shared_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t head_dim,
+                                        int32_t max_blocks_per_seq)
 {
-    if (num_seqs <= 0 || num_heads <= 0 || head_dim <= 0) return 0;
-    const size_t partials = (size_t)num_seqs * num_heads * 2 * ((size_t)head_dim + 2) * sizeof(float);
-    return partials + ((ginfo_words(num_seqs) * sizeof(int32_t) + 15) & ~(size_t)15);
+    if (num_seqs <= 0 || num_heads <= 0 || head_dim <= 0 || max_blocks_per_seq <= 0) return 0;
+    return ginfo_bytes(num_seqs) + (size_t)num_seqs * max_blocks_per_seq * sizeof(int2);
 }
 
 pa_status pa_decode_shared(void *out, const void *q, const void *k_cache, const void *v_cache,
@@ -328,7 +338,12 @@ pa_status pa_decode_shared(void *out, const void *q, const void *k_cache, const 
     if (!out || !q || !k_cache || !v_cache || !block_tables || !context_lens) return PA_ERR_NULL;
     if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return PA_ERR_ALIGN;
     if ((int64_t)num_seqs * num_heads > (int64_t)0x7fffffff / 64) return PA_ERR_SHAPE;
-    const size_t need = pa_decode_shared_workspace_bytes(num_seqs, num_heads, head_dim);
+    if (!shared_on_matrix_cores(dtype, head_dim, block_size, max_blocks_per_seq))
+        // no several-query kernel for this shape: the plain one-pass kernel gives the same result
+        return pa_decode(out, q, k_cache, v_cache, block_tables, max_blocks_per_seq, context_lens, num_seqs,
+                         num_heads, head_dim, block_size, num_blocks, dtype, scale, max_context_len, 0,
+                         nullptr, 0, stream);
+    const size_t need = pa_decode_shared_workspace_bytes(num_seqs, num_heads, head_dim, max_blocks_per_seq);
     if (!workspace || workspace_bytes < need) return PA_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PA_ERR_ALIGN;
 
@@ -336,13 +351,11 @@ pa_status pa_decode_shared(void *out, const void *q, const void *k_cache, const 
     memset(&a, 0, sizeof(a));
     fill_common(a, out, q, k_cache, v_cache, block_tables, max_blocks_per_seq, context_lens, num_seqs,
                 num_heads, scale, stream);
-    a.p.max_parts = 2;
+    a.p.max_parts = 1;
     a.waves = waves_for(max_context_len, chunk_tokens(dtype, head_dim, block_size));
-    const size_t rows2 = (size_t)num_seqs * num_heads * 2;
-    a.p.ws_acc = static_cast<float *>(workspace);
-    a.p.ws_ml = a.p.ws_acc + rows2 * head_dim;
-    a.p.ginfo = reinterpret_cast<const int32_t *>(a.p.ws_ml + rows2 * 2);
-    if (!dispatch_decode(a, dtype, head_dim, block_size, MODE_PREFIX)) return PA_ERR_UNSUPPORTED;
+    a.p.ginfo = static_cast<const int32_t *>(workspace);
+    a.p.tiles = reinterpret_cast<const int2 *>(static_cast<const char *>(workspace) + ginfo_bytes(num_seqs));
+    if (!dispatch_decode(a, dtype, head_dim, block_size, PLAN_SHARED)) return PA_ERR_UNSUPPORTED;
     return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
 }
 

@@ -20,8 +20,7 @@ constexpr int kWave = 64;
 // chunks requested together per trip of the steady-state loop
 constexpr int kChunksPerTrip = PA_CHUNKS_PER_TRIP;
 constexpr int kChunksPerTripDevice = PA_CHUNKS_PER_TRIP;
-constexpr int kGroupMax = 4;       // query slots of the VALU shared-prefix kernel
-constexpr int kGroupMaxMfma = 8;   // query slots used of the 16 rows of the MFMA shared-prefix kernel
+constexpr int kGroupMaxMfma = 8;   // members of a shared group (of the 16 query rows of the MFMA tiles)
 constexpr float kLog2e = 1.4426950408889634f;
 // running-maximum start value: finite, so that (m - m) is 0 and never NaN
 constexpr float kNegBig = -3.0e38f;

@@ -1,4 +1,4 @@
-// libpa paged decode: the VALU decode kernel (one pass, fixed partitions, suffix, shared prefix) and the merge kernel.
+// libpa paged decode: the VALU decode kernel (one pass or fixed partitions) and the merge kernel.
 #ifndef PA_PA_DECODE_HPP
 #define PA_PA_DECODE_HPP
 
@@ -8,9 +8,7 @@ namespace {
 
 // ---- decode ----------------------------------------------------------------
 // One workgroup of W wavefronts serves one work item: a (sequence, head) over
-// its whole context, over one fixed-size partition of it, or over the suffix
-// that follows a shared prefix; or a (group of sequences, head) over the
-// prefix of physical blocks the group has in common.
+// its whole context, or over one fixed-size partition of it.
 //
 // Lane roles: a token row is LPT = D*E/16 lanes wide, so one 1 KiB wavefront
 // load covers TPL = 64/LPT consecutive tokens; lane = g*LPT + c holds
@@ -25,16 +23,9 @@ namespace {
 // the end with the log-sum-exp rule, so the inner loop has no cross-group
 // traffic.  Summation order depends only on logical token positions, so the
 // result does not change with the physical placement of blocks.
-//
-// In the shared-prefix mode the workgroup holds the queries of up to G
-// sequences and applies every K/V fragment it loads to all of them, so blocks
-// that several sequences map (parallel sampling, beam search: Sec. 4.4) are
-// read from memory once per group instead of once per sequence.
 enum DecodeMode {
     MODE_SINGLE = 0,   // whole context, writes the output row
-    MODE_PART = 1,     // tokens [part*PS, (part+1)*PS), writes partial `part` of max_parts
-    MODE_SUFFIX = 2,   // tokens [range_begin[s], n), writes partial 1 of 2
-    MODE_PREFIX = 3    // tokens [0, prefix) of a group, writes partial 0 of 2 for every member
+    MODE_PART = 1      // tokens [part*PS, (part+1)*PS), writes partial `part` of max_parts
 };
 
 struct DecodeParams {
@@ -43,25 +34,26 @@ struct DecodeParams {
     const char *k_cache, *v_cache;
     const int32_t *block_tables;
     const int32_t *context_lens;
-    const int32_t *ginfo;   // group table built by find_groups_kernel (shared-prefix path)
+    const int32_t *ginfo;   // group table built by find_groups_kernel (pa_decode_shared)
+    const int2 *tiles;      // per-group tile lists built by build_tiles_kernel
     const int32_t *q_start; // multi-query path: first query row of every sequence, [S+1]
     float *ws_acc, *ws_ml;
     int32_t max_blocks, S, H;
     int32_t partition_size, max_parts;
-    int32_t prefix_blocks;   // fused shared-prefix launch: workgroups [0, prefix_blocks) are prefix items
+    int32_t group_blocks;    // fused shared launch: workgroups [0, group_blocks) are group items
     int32_t q_blocks;        // multi-query path: blocks of 16 queries per sequence in the grid
     float scale_log2;
 };
 
-// Layout of the group table, three arrays of S entries: range_begin[s] (tokens
-// of s covered by its group's shared prefix), group_size[s] (members of the
-// group that starts at sequence s, 0 if none starts there) and
-// group_prefix_tokens[s] (tokens all members of that group have in common).
-__device__ __host__ __forceinline__ int ginfo_range_begin(int S, int s) { (void)S; return s; }
+// Layout of the group table of pa_decode_shared, arrays of S int32 entries:
+// in_group[s] (1 if s belongs to a group of two or more), group_size[s] (members
+// of the group that starts at sequence s, 0 if none starts there), tile_count[s]
+// (entries of that group's tile list), adj[s] (scratch of the discovery), the
+// compact list of the first sequences of shared groups, and its length.
+__device__ __host__ __forceinline__ int ginfo_in_group(int S, int s) { (void)S; return s; }
 __device__ __host__ __forceinline__ int ginfo_group_size(int S, int s) { return S + s; }
-__device__ __host__ __forceinline__ int ginfo_group_prefix(int S, int s) { return 2 * S + s; }
+__device__ __host__ __forceinline__ int ginfo_tile_count(int S, int s) { return 2 * S + s; }
 __device__ __host__ __forceinline__ int ginfo_adj(int S, int s) { return 3 * S + s; }
-// compact list of the first sequences of groups with two or more members, and its length
 __device__ __host__ __forceinline__ int ginfo_shared_list(int S, int i) { return 4 * S + i; }
 __device__ __host__ __forceinline__ int ginfo_shared_count(int S) { return 5 * S; }
 __device__ __host__ __forceinline__ size_t ginfo_words(int S) { return 5 * (size_t)S + 4; }
@@ -71,8 +63,7 @@ __device__ __host__ __forceinline__ size_t ginfo_words(int S) { return 5 * (size
 // lengths, two resident workgroups each run at half speed and stretch the end
 // of the launch by more than their overlap gains.
 #define PA_OCC_ATTR __attribute__((amdgpu_waves_per_eu(W == 16 ? 4 : 1, W == 16 ? 7 : 8)))
-#define PA_OCC_ATTR_FUSED __attribute__((amdgpu_waves_per_eu(WS == 16 ? 4 : 1, WS == 16 ? 7 : 8)))
-template <int DT, int D, int B, int W, int U, int MODE, int G>
+template <int DT, int D, int B, int W, int U, int MODE>
 __device__ __forceinline__ void decode_body(const DecodeParams &P, const int block_index)
 {
     using Tr = Traits<DT>;
@@ -84,7 +75,6 @@ __device__ __forceinline__ void decode_body(const DecodeParams &P, const int blo
     constexpr int CT = LPC * TPL;
     constexpr int64_t TILE_BYTES = (int64_t)B * ROW_BYTES;
     static_assert(LPT >= 8 && LPT <= 32 && B % TPL == 0 && B % CT == 0 && LPC >= 1, "shape");
-    static_assert(G == 1 || MODE == MODE_PREFIX, "several queries only in the shared-prefix mode");
 
     const int lane = threadIdx.x & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -96,33 +86,12 @@ __device__ __forceinline__ void decode_body(const DecodeParams &P, const int blo
     int item = block_index;
     const int h = item % H;
     item /= H;
+    const int part = MODE == MODE_PART ? item % P.max_parts : 0;
+    const int s = MODE == MODE_PART ? item / P.max_parts : item;
 
-    // s: the sequence whose block table is walked; members: query slots in use
-    int s, part = 0, parts_stride = 1, t_begin = 0, t_end, members = 1;
-    if (MODE == MODE_PREFIX) {
-        if (item >= P.ginfo[ginfo_shared_count(P.S)]) return;
-        s = P.ginfo[ginfo_shared_list(P.S, item)];   // a group is named by its first sequence
-        members = P.ginfo[ginfo_group_size(P.S, s)];
-        t_end = P.ginfo[ginfo_group_prefix(P.S, s)];
-        parts_stride = 2;
-        if (members < 2) return;
-    } else if (MODE == MODE_SUFFIX) {
-        s = item;
-        t_begin = P.ginfo[ginfo_range_begin(P.S, s)];
-        t_end = P.context_lens[s];
-        part = 1;
-        parts_stride = 2;
-    } else if (MODE == MODE_PART) {
-        part = item % P.max_parts;
-        s = item / P.max_parts;
-        parts_stride = P.max_parts;
-        const int n = P.context_lens[s];
-        t_begin = part * P.partition_size;
-        t_end = t_begin + P.partition_size < n ? t_begin + P.partition_size : n;
-    } else {
-        s = item;
-        t_end = P.context_lens[s];
-    }
+    const int n = P.context_lens[s];
+    const int t_begin = MODE == MODE_PART ? part * P.partition_size : 0;
+    const int t_end = MODE == MODE_PART ? (t_begin + P.partition_size < n ? t_begin + P.partition_size : n) : n;
     if (t_begin >= t_end) {
         if (MODE == MODE_SINGLE && w == 0 && g == 0) {
             // empty context: zero row
@@ -131,24 +100,14 @@ __device__ __forceinline__ void decode_body(const DecodeParams &P, const int blo
         return;
     }
 
-    // members of a group are consecutive sequences s, s+1, ...
-    uint4 qf[G];
-#pragma unroll
-    for (int j = 0; j < G; ++j) {
-        const int sj = j < members ? s + j : s;
-        qf[j] = reinterpret_cast<const uint4 *>(P.q)[((int64_t)sj * H + h) * LPT + c];
-    }
+    const uint4 qf = reinterpret_cast<const uint4 *>(P.q)[((int64_t)s * H + h) * LPT + c];
     const int32_t *__restrict__ table = P.block_tables + (int64_t)s * P.max_blocks;
     const int nchunks = (t_end - t_begin + CT - 1) / CT;
 
-    float m[G], l[G], acc[G][EPL];
+    float m = kNegBig, l = 0.f;
+    float acc[EPL];
 #pragma unroll
-    for (int j = 0; j < G; ++j) {
-        m[j] = kNegBig;
-        l[j] = 0.f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[j][e] = 0.f;
-    }
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
 
     struct Chunk {
         uint4 k[LPC], v[LPC];
@@ -172,51 +131,42 @@ __device__ __forceinline__ void decode_body(const DecodeParams &P, const int blo
     auto consume = [&](Chunk &ck, int ci, auto mask_tag) {
         constexpr bool MASK = decltype(mask_tag)::value;
         const int t0 = t_begin + ci * CT;
+        float x[LPC];
+#pragma unroll
+        for (int i = 0; i < LPC; ++i) x[i] = group_sum<LPT>(Tr::dot(ck.k[i], qf, 0.f)) * P.scale_log2;
         if (MASK) {
             // slots at or past t_end hold no token and may contain anything, NaN
             // included - select them away, never multiply
 #pragma unroll
             for (int i = 0; i < LPC; ++i) {
                 const bool dead = t0 + i * TPL + g >= t_end;
+                x[i] = dead ? -INFINITY : x[i];
                 ck.v[i].x = dead ? 0u : ck.v[i].x;
                 ck.v[i].y = dead ? 0u : ck.v[i].y;
                 ck.v[i].z = dead ? 0u : ck.v[i].z;
                 ck.v[i].w = dead ? 0u : ck.v[i].w;
             }
         }
+        float m_new = m;
 #pragma unroll
-        for (int j = 0; j < G; ++j) {
-            if (G > 1 && j >= members) break;
-            float x[LPC];
+        for (int i = 0; i < LPC; ++i) m_new = fmaxf(m_new, x[i]);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        float p[LPC], psum = 0.f;
 #pragma unroll
-            for (int i = 0; i < LPC; ++i) x[i] = group_sum<LPT>(Tr::dot(ck.k[i], qf[j], 0.f)) * P.scale_log2;
-            if (MASK) {
+        for (int i = 0; i < LPC; ++i) {
+            p[i] = __builtin_amdgcn_exp2f(x[i] - m_new);
+            psum += p[i];
+        }
+        l = l * alpha + psum;
+        m = m_new;
 #pragma unroll
-                for (int i = 0; i < LPC; ++i) x[i] = (t0 + i * TPL + g >= t_end) ? -INFINITY : x[i];
-            }
-            float m_new = m[j];
+        for (int e = 0; e < EPL; ++e) acc[e] *= alpha;
 #pragma unroll
-            for (int i = 0; i < LPC; ++i) m_new = fmaxf(m_new, x[i]);
-            const float alpha = __builtin_amdgcn_exp2f(m[j] - m_new);
-            float p[LPC], psum = 0.f;
-#pragma unroll
-            for (int i = 0; i < LPC; ++i) {
-                p[i] = __builtin_amdgcn_exp2f(x[i] - m_new);
-                psum += p[i];
-            }
-            l[j] = l[j] * alpha + psum;
-            m[j] = m_new;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[j][e] *= alpha;
-#pragma unroll
-            for (int i = 0; i < LPC; ++i) {
-                Tr::axpy(acc[j], p[i], ck.v[i]);
-                // bf16 widening is two VALU ops per pair; without a fence the
-                // scheduler widens every fragment first and doubles the live registers
-                if (Tr::FENCE_AXPY) __builtin_amdgcn_sched_barrier(0);
-            }
-            // one member at a time: interleaving their arithmetic multiplies the live registers
-            if (G > 1) __builtin_amdgcn_sched_barrier(0);
+        for (int i = 0; i < LPC; ++i) {
+            Tr::axpy(acc, p[i], ck.v[i]);
+            // bf16 widening is two VALU ops per pair; without a fence the
+            // scheduler widens every fragment first and doubles the live registers
+            if (Tr::FENCE_AXPY) __builtin_amdgcn_sched_barrier(0);
         }
     };
     const std::false_type full{};
@@ -248,97 +198,81 @@ __device__ __forceinline__ void decode_body(const DecodeParams &P, const int blo
     }
 
     // merge the TPL token groups of this wave (lanes with equal c)
-#pragma unroll
-    for (int j = 0; j < G; ++j) {
-        float M = m[j];
+    {
+        float M = m;
 #pragma unroll
         for (int d = LPT; d < kWave; d <<= 1) M = fmaxf(M, __shfl_xor(M, d));
-        const float f = __builtin_amdgcn_exp2f(m[j] - M);
-        l[j] *= f;
+        const float f = __builtin_amdgcn_exp2f(m - M);
+        l *= f;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[j][e] *= f;
+        for (int e = 0; e < EPL; ++e) acc[e] *= f;
 #pragma unroll
         for (int d = LPT; d < kWave; d <<= 1) {
-            l[j] += __shfl_xor(l[j], d);
+            l += __shfl_xor(l, d);
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[j][e] += __shfl_xor(acc[j][e], d);
+            for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], d);
         }
-        m[j] = M;
+        m = M;
     }
 
     // merge the W waves of the workgroup through LDS
     if (W > 1) {
-        __shared__ float sm_acc[W][G][D];
-        __shared__ float sm_m[W][G], sm_l[W][G];
+        __shared__ float sm_acc[W][D];
+        __shared__ float sm_m[W], sm_l[W];
         if (g == 0) {
 #pragma unroll
-            for (int j = 0; j < G; ++j) {
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) sm_acc[w][j][c * EPL + e] = acc[j][e];
-                if (c == 0) {
-                    sm_m[w][j] = m[j];
-                    sm_l[w][j] = l[j];
-                }
+            for (int e = 0; e < EPL; ++e) sm_acc[w][c * EPL + e] = acc[e];
+            if (c == 0) {
+                sm_m[w] = m;
+                sm_l[w] = l;
             }
         }
         __syncthreads();
         if (w != 0) return;
+        float M = sm_m[0];
 #pragma unroll
-        for (int j = 0; j < G; ++j) {
-            float M = sm_m[0][j];
+        for (int i = 1; i < W; ++i) M = fmaxf(M, sm_m[i]);
+        l = 0.f;
 #pragma unroll
-            for (int i = 1; i < W; ++i) M = fmaxf(M, sm_m[i][j]);
-            l[j] = 0.f;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[j][e] = 0.f;
-            // (not fully unrolled: sixteen waves' worth of LDS reads hoisted at once would spill)
+        for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+        // (not fully unrolled: sixteen waves' worth of LDS reads hoisted at once would spill)
 #pragma unroll 2
-            for (int i = 0; i < W; ++i) {
-                const float f = __builtin_amdgcn_exp2f(sm_m[i][j] - M);
-                l[j] = __builtin_fmaf(sm_l[i][j], f, l[j]);
+        for (int i = 0; i < W; ++i) {
+            const float f = __builtin_amdgcn_exp2f(sm_m[i] - M);
+            l = __builtin_fmaf(sm_l[i], f, l);
 #pragma unroll
-                for (int e = 0; e < EPL; ++e)
-                    acc[j][e] = __builtin_fmaf(sm_acc[i][j][c * EPL + e], f, acc[j][e]);
-            }
-            m[j] = M;
+            for (int e = 0; e < EPL; ++e) acc[e] = __builtin_fmaf(sm_acc[i][c * EPL + e], f, acc[e]);
         }
+        m = M;
     }
     if (g != 0) return;
 
     if (MODE == MODE_SINGLE) {
-        const float inv = 1.0f / l[0];
+        const float inv = 1.0f / l;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[0][e] *= inv;
-        reinterpret_cast<uint4 *>(P.out)[((int64_t)s * H + h) * LPT + c] = Tr::pack(acc[0]);
+        for (int e = 0; e < EPL; ++e) acc[e] *= inv;
+        reinterpret_cast<uint4 *>(P.out)[((int64_t)s * H + h) * LPT + c] = Tr::pack(acc);
     } else {
-        // unnormalised partials: the reduce kernel divides once
+        // unnormalised partial: the reduce kernel divides once
+        const int64_t slot = ((int64_t)s * H + h) * P.max_parts + part;
+        float *dst = P.ws_acc + slot * D + c * EPL;
 #pragma unroll
-        for (int j = 0; j < G; ++j) {
-            if (j >= members) break;
-            const int64_t slot = ((int64_t)(s + j) * H + h) * parts_stride + part;
-            float *dst = P.ws_acc + slot * D + c * EPL;
-#pragma unroll
-            for (int e = 0; e < EPL; e += 4)
-                *reinterpret_cast<float4 *>(dst + e) =
-                    make_float4(acc[j][e], acc[j][e + 1], acc[j][e + 2], acc[j][e + 3]);
-            if (c == 0) *reinterpret_cast<float2 *>(P.ws_ml + slot * 2) = make_float2(m[j], l[j]);
-        }
+        for (int e = 0; e < EPL; e += 4)
+            *reinterpret_cast<float4 *>(dst + e) = make_float4(acc[e], acc[e + 1], acc[e + 2], acc[e + 3]);
+        if (c == 0) *reinterpret_cast<float2 *>(P.ws_ml + slot * 2) = make_float2(m, l);
     }
 }
 
-template <int DT, int D, int B, int W, int U, int MODE, int G>
+template <int DT, int D, int B, int W, int U, int MODE>
 __global__ __launch_bounds__(W *kWave) PA_OCC_ATTR void pa_decode_kernel(const DecodeParams P)
 {
-    decode_body<DT, D, B, W, U, MODE, G>(P, (int)blockIdx.x);
+    decode_body<DT, D, B, W, U, MODE>(P, (int)blockIdx.x);
 }
 
-// Merge of partials: out = sum_p 2^(m_p-M) a_p / sum_p 2^(m_p-M) l_p with a_p the
-// unnormalised partial sums.  One wavefront per (sequence, head); lane c
-// handles the same 16-byte output fragment as in the decode kernel.  With
-// fixed partitions the first ceil(n/PS) partials exist; on the shared-prefix
-// path partial 0 (prefix) exists when range_begin[s] > 0 and partial 1
-// (suffix) when range_begin[s] < n.
-template <int DT, int D, bool SHARED>
+// Merge of the split-context partials: out = sum_p 2^(m_p-M) a_p / sum_p 2^(m_p-M) l_p
+// with a_p the unnormalised partial sums.  One wavefront per (sequence, head);
+// lane c handles the same 16-byte output fragment as in the decode kernel.
+template <int DT, int D>
 __global__ __launch_bounds__(kWave) void pa_reduce_kernel(const DecodeParams P)
 {
     using Tr = Traits<DT>;
@@ -350,26 +284,17 @@ __global__ __launch_bounds__(kWave) void pa_reduce_kernel(const DecodeParams P)
     const int h = blockIdx.x % H;
     const int s = blockIdx.x / H;
     const int n = P.context_lens[s];
-    int first = 0, last, stride;
-    if (SHARED) {
-        const int rb = P.ginfo[ginfo_range_begin(P.S, s)];
-        stride = 2;
-        first = rb > 0 ? 0 : 1;
-        last = n > rb ? 2 : 1;
-    } else {
-        stride = P.max_parts;
-        last = (n + P.partition_size - 1) / P.partition_size;
-        if (last > stride) last = stride;
-    }
-    const int64_t base = ((int64_t)s * H + h) * stride;
+    int parts = (n + P.partition_size - 1) / P.partition_size;
+    if (parts > P.max_parts) parts = P.max_parts;
+    const int64_t base = ((int64_t)s * H + h) * P.max_parts;
     float acc[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
-    if (n > 0 && first < last) {
+    if (parts > 0) {
         float M = kNegBig;
-        for (int p = first; p < last; ++p) M = fmaxf(M, P.ws_ml[(base + p) * 2]);
+        for (int p = 0; p < parts; ++p) M = fmaxf(M, P.ws_ml[(base + p) * 2]);
         float l = 0.f;
-        for (int p = first; p < last; ++p) {
+        for (int p = 0; p < parts; ++p) {
             const float2 ml = *reinterpret_cast<const float2 *>(P.ws_ml + (base + p) * 2);
             const float f = __builtin_amdgcn_exp2f(ml.x - M);
             l = __builtin_fmaf(ml.y, f, l);
@@ -389,7 +314,6 @@ __global__ __launch_bounds__(kWave) void pa_reduce_kernel(const DecodeParams P)
     }
     reinterpret_cast<uint4 *>(P.out)[((int64_t)s * H + h) * LPT + c] = Tr::pack(acc);
 }
-
 
 } // namespace
 

@@ -1,4 +1,4 @@
-// libpa group discovery for pa_decode_shared.
+// libpa group discovery and tile lists for pa_decode_shared.
 #ifndef PA_PA_GROUPS_HPP
 #define PA_PA_GROUPS_HPP
 
@@ -6,46 +6,33 @@
 
 namespace {
 
-// Group discovery for the shared-prefix path.  Consecutive sequences whose
-// block tables start with the same physical blocks form a group (that is how
-// forked sequences sit in a batch: samples of one prompt, beams of one
-// search).  Only blocks that are full for both neighbours count, so every
-// token of a shared prefix is valid for every member.
-//   adj[s] = leading blocks s has in common with s-1 (0 for s = 0).
+// Group discovery.  Consecutive sequences whose block tables start with the
+// same physical blocks form a group (that is how forked sequences sit in a
+// batch: samples of one prompt, beams of one search).
+//   adj[s] = leading full blocks s has in common with s-1 (0 for s = 0).
 // A sequence with adj = 0 starts a run; runs are independent, so one thread
-// walks each run: a sequence joins the current group while the group has room
-// and the common prefix would keep at least three quarters of its length,
-// otherwise it starts a new group.  One workgroup, state in LDS when it fits.
+// walks each run, closing a group when it has group_max members.  Groups of
+// two or more are listed compactly (shared_list / shared_count); their
+// members are flagged in in_group[].  One workgroup, state in LDS when it fits.
 constexpr int kGroupScanLds = 2048;   // sequences whose scan state fits in LDS
 constexpr int kGroupThreads = 1024;
 
-__device__ __forceinline__ void group_walk_run(const int32_t *adj, int32_t *range_begin, int32_t *g_size,
-                                               int32_t *g_prefix, int first, int S, int block_size,
-                                               int group_max)
+__device__ __forceinline__ void group_walk_run(const int32_t *adj, int32_t *in_group, int32_t *g_size,
+                                               int first, int S, int group_max)
 {
-    int start = first, size = 1, prefix = 0;
+    int start = first, size = 1;
     auto close = [&]() {
-        const int tokens = size > 1 ? prefix * block_size : 0;
         g_size[start] = size;
-        g_prefix[start] = tokens;
-        for (int j = 0; j < size; ++j) range_begin[start + j] = tokens;
+        for (int j = 0; j < size; ++j) in_group[start + j] = size > 1;
     };
     for (int sq = first + 1; sq < S; ++sq) {
-        const int a = adj[sq];
-        if (a == 0) break;   // the next run belongs to another thread
-        bool join = false;
+        if (adj[sq] == 0) break;   // the next run belongs to another thread
         if (size < group_max) {
-            const int np = size == 1 ? a : (a < prefix ? a : prefix);
-            join = size == 1 || 4 * np >= 3 * prefix;
-            if (join) prefix = np;
-        }
-        if (join) {
             ++size;
         } else {
             close();
             start = sq;
             size = 1;
-            prefix = 0;
         }
     }
     close();
@@ -56,8 +43,7 @@ __global__ __launch_bounds__(kGroupThreads) void find_groups_kernel(
     const int32_t *__restrict__ context_lens, int32_t S, int32_t block_size, int32_t group_max,
     int32_t *__restrict__ ginfo)
 {
-    __shared__ int32_t s_adj[kGroupScanLds], s_range[kGroupScanLds], s_size[kGroupScanLds],
-        s_prefix[kGroupScanLds];
+    __shared__ int32_t s_adj[kGroupScanLds], s_in[kGroupScanLds], s_size[kGroupScanLds];
     const bool in_lds = S <= kGroupScanLds;
 
     // adj[s]: one wavefront compares the table rows of s-1 and s, 64 entries per
@@ -86,24 +72,9 @@ __global__ __launch_bounds__(kGroupThreads) void find_groups_kernel(
         for (int u = 0; u < UN; ++u) {
             const int sq = base + u;
             if (sq >= S) break;
-            int a = 0;
-            unsigned long long diff = __ballot(lane < lim[u] && e0[u] != e1[u]);
-            if (diff) {
-                a = __builtin_ctzll(diff);
-            } else {
-                a = lim[u] < kWave ? lim[u] : kWave;
-                // the first 64 blocks all agree: keep comparing (long shared prefixes)
-                for (int j0 = kWave; j0 < lim[u] && a == j0; j0 += kWave) {
-                    const int j = j0 + lane;
-                    bool ne = false;
-                    if (j < lim[u])
-                        ne = block_tables[(int64_t)(sq - 1) * max_blocks + j] !=
-                             block_tables[(int64_t)sq * max_blocks + j];
-                    diff = __ballot(ne);
-                    const int rest = lim[u] - j0 < kWave ? lim[u] - j0 : kWave;
-                    a = j0 + (diff ? (int)__builtin_ctzll(diff) : rest);
-                }
-            }
+            // only "some block in common" matters here: the first 64 entries decide
+            const unsigned long long diff = __ballot(lane < lim[u] && e0[u] != e1[u]);
+            const int a = diff ? (int)__builtin_ctzll(diff) : (lim[u] < kWave ? lim[u] : kWave);
             if (lane == 0) {
                 if (in_lds) {
                     s_adj[sq] = a;
@@ -118,23 +89,20 @@ __global__ __launch_bounds__(kGroupThreads) void find_groups_kernel(
     __syncthreads();
     if (in_lds) {
         for (int sq = threadIdx.x; sq < S; sq += kGroupThreads)
-            if (s_adj[sq] == 0) group_walk_run(s_adj, s_range, s_size, s_prefix, sq, S, block_size, group_max);
+            if (s_adj[sq] == 0) group_walk_run(s_adj, s_in, s_size, sq, S, group_max);
         __syncthreads();
         for (int i = threadIdx.x; i < S; i += kGroupThreads) {
-            ginfo[ginfo_range_begin(S, i)] = s_range[i];
+            ginfo[ginfo_in_group(S, i)] = s_in[i];
             ginfo[ginfo_group_size(S, i)] = s_size[i];
-            ginfo[ginfo_group_prefix(S, i)] = s_size[i] ? s_prefix[i] : 0;
         }
     } else {
         for (int sq = threadIdx.x; sq < S; sq += kGroupThreads)
             if (ginfo[ginfo_adj(S, sq)] == 0)
-                group_walk_run(ginfo + ginfo_adj(S, 0), ginfo + ginfo_range_begin(S, 0),
-                               ginfo + ginfo_group_size(S, 0), ginfo + ginfo_group_prefix(S, 0), sq, S,
-                               block_size, group_max);
+                group_walk_run(ginfo + ginfo_adj(S, 0), ginfo + ginfo_in_group(S, 0),
+                               ginfo + ginfo_group_size(S, 0), sq, S, group_max);
     }
     __syncthreads();
-    // compact the first sequences of shared groups (two or more members), in order, so that
-    // the prefix kernel's workgroups with work come first in its grid
+    // compact the first sequences of shared groups (two or more members), in order
     __shared__ int32_t wave_count[NW];
     __shared__ int32_t running;
     if (threadIdx.x == 0) running = 0;
@@ -159,6 +127,86 @@ __global__ __launch_bounds__(kGroupThreads) void find_groups_kernel(
     if (threadIdx.x == 0) ginfo[ginfo_shared_count(S)] = running;
 }
 
+// Tile list of a shared group: every distinct physical block its members map,
+// once, with the set of members that map it.  Forked sequences share a block
+// only at the same logical position, so the members' tables are compared
+// position by position: lane i of the group's wavefront looks at logical block
+// base+i of all members, keeps the first member of every set of equal ids and
+// records (block id, member mask, tokens stored in the block, position).  A
+// wave-wide prefix sum of the per-position counts places the entries, in
+// position order, at tiles[first_sequence * max_blocks ...].
+//   entry.x = physical block,
+//   entry.y = mask | tokens << 8 | position << 16 | ragged << 31, where ragged says that
+//             some member mapping the block sees fewer tokens of it than the block holds
+constexpr int kTileWaves = 4;
+__global__ __launch_bounds__(kTileWaves *kWave) void build_tiles_kernel(
+    const int32_t *__restrict__ block_tables, int32_t max_blocks,
+    const int32_t *__restrict__ context_lens, int32_t S, int32_t block_size,
+    int32_t *__restrict__ ginfo, int2 *__restrict__ tiles)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int gi = blockIdx.x * kTileWaves + (int)(threadIdx.x / kWave);
+    if (gi >= ginfo[ginfo_shared_count(S)]) return;
+    const int start = ginfo[ginfo_shared_list(S, gi)];
+    const int G = ginfo[ginfo_group_size(S, start)];
+    int n[kGroupMaxMfma], nb[kGroupMaxMfma], maxnb = 0;
+#pragma unroll
+    for (int j = 0; j < kGroupMaxMfma; ++j) {
+        n[j] = j < G ? context_lens[start + j] : 0;
+        nb[j] = (n[j] + block_size - 1) / block_size;
+        maxnb = nb[j] > maxnb ? nb[j] : maxnb;
+    }
+    int2 *out = tiles + (int64_t)start * max_blocks;
+    int placed = 0;
+    for (int base = 0; base < maxnb; base += kWave) {
+        const int i = base + lane;
+        int id[kGroupMaxMfma];
+#pragma unroll
+        for (int j = 0; j < kGroupMaxMfma; ++j)
+            id[j] = i < nb[j] ? block_tables[(int64_t)(start + j) * max_blocks + i] : -1 - j;
+        uint32_t firsts = 0, mask[kGroupMaxMfma];
+        int nmax[kGroupMaxMfma], nmin[kGroupMaxMfma];
+#pragma unroll
+        for (int j = 0; j < kGroupMaxMfma; ++j) {
+            mask[j] = 0;
+            nmax[j] = 0;
+            nmin[j] = 0x7fffffff;
+            bool first = i < nb[j];
+#pragma unroll
+            for (int j2 = 0; j2 < kGroupMaxMfma; ++j2) {
+                const bool same = i < nb[j2] && id[j2] == id[j];
+                if (same) {
+                    mask[j] |= 1u << j2;
+                    nmax[j] = n[j2] > nmax[j] ? n[j2] : nmax[j];
+                    nmin[j] = n[j2] < nmin[j] ? n[j2] : nmin[j];
+                    if (j2 < j) first = false;
+                }
+            }
+            if (first) firsts |= 1u << j;
+        }
+        const int count = __builtin_popcount(firsts);
+        int incl = count;   // inclusive prefix sum over lanes
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int up = __shfl_up(incl, d);
+            if (lane >= d) incl += up;
+        }
+        const int total = __shfl(incl, kWave - 1);
+        const int at = placed + incl - count;
+#pragma unroll
+        for (int j = 0; j < kGroupMaxMfma; ++j) {
+            if ((firsts >> j) & 1u) {
+                int tokens = nmax[j] - i * block_size;
+                tokens = tokens < block_size ? tokens : block_size;
+                const uint32_t ragged = nmin[j] < (i + 1) * block_size ? 1u : 0u;
+                out[at + __builtin_popcount(firsts & ((1u << j) - 1u))] =
+                    make_int2(id[j], (int)(mask[j] | ((uint32_t)tokens << 8) | ((uint32_t)i << 16) | (ragged << 31)));
+            }
+        }
+        placed += total;
+    }
+    if (lane == 0) ginfo[ginfo_tile_count(S, start)] = placed;
+}
 
 } // namespace
 

@@ -6,19 +6,25 @@
 
 namespace {
 
-// ---- shared-prefix decode on the matrix cores --------------------------------
-// A group's common prefix is a small dense contraction: up to 16 queries against
-// 16-token K/V tiles.  One workgroup per (group, head); wave w takes tiles
-// w, w+W, ...  Per tile:
+// ---- several queries against shared K/V tiles, on the matrix cores -----------
+// Where several queries meet the same K/V tile the work is a small dense
+// contraction: up to 16 queries against 16-token tiles.  Two uses:
+//   GROUP  a group of sequences that map common physical blocks (Sec. 4.4):
+//          one workgroup per (group, head) walks the group's tile list - every
+//          distinct block once, with the set of members that map it - and
+//          produces the finished output row of every member;
+//   MULTI  the last q_len tokens of one sequence as causal queries.
+// Wave w takes tiles w, w+W, ...  Per 16-token tile:
 //   S^T = K Q^T   8 x v_mfma_f32_16x16x16 (f16 or bf16 operands, fp32 result):
 //                 A rows are tokens, B columns are queries.  Lane l supplies
 //                 row l%16; each of its four 16-byte loads feeds two MFMAs,
 //                 with the same (arbitrary but consistent) assignment of head
 //                 dimensions to contraction slots on the Q side.
 //   softmax       the result leaves lane l with query l%16 and four tokens;
-//                 the running maximum is kept per query (two cross-lane maxima
-//                 per tile), exp2 in fp32, rescaling of the output only when
-//                 some maximum moved.
+//                 entries of queries that do not map the block, or of tokens a
+//                 query does not see, are set to -inf by select; the running
+//                 maximum is kept per query (two cross-lane maxima per tile),
+//                 exp2 in fp32, the output rescaled only when a maximum moved.
 //   O += P V      32 x v_mfma_f32_16x16x4_f32: A = P in fp32 straight from the
 //                 softmax registers, B = the V fragments of the ordinary
 //                 coalesced load widened to fp32 (lane l: token l/16 + 4v,
@@ -27,8 +33,7 @@ namespace {
 //                 rate is still about three times what the HBM stream needs.
 // K rows are loaded in the order token(i) = i/4 + 4*(i%4) so that result
 // register v of lane l belongs to token l/16 + 4v, the token of V fragment v
-// in that lane: P never moves between lanes.
-// Outputs: the same unnormalised partials as MODE_PREFIX (partial 0 of 2).
+// in that lane: P never moves between lanes and V needs no transpose.
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
@@ -62,15 +67,11 @@ __device__ __forceinline__ void widen8(float (&f)[8], const uint4 &v)
     }
 }
 
-// MULTI = false: a group's shared prefix (GQ = 8 query slots, partial results).
-// MULTI = true:  the last q_len tokens of ONE sequence as queries over its whole
-//                context, 16 per workgroup, with the causal rule that query i of the
-//                q_len new tokens sees tokens 0 .. n - q_len + i; writes output rows.
 template <int DT, int B, int W, int GQ, bool MULTI>
-__device__ __forceinline__ void prefix_mfma_body(const DecodeParams &P, const int block_index)
+__device__ __forceinline__ void mfma_body(const DecodeParams &P, const int block_index)
 {
     using Tr = Traits<DT>;
-    constexpr int D = 128, ROW_BYTES = 256;
+    constexpr int D = 128, ROW_BYTES = 256, SUBS = B / 16;
     constexpr int64_t TILE_BYTES = (int64_t)B * ROW_BYTES;
     static_assert(DT != PA_F32 && B % 16 == 0, "two-byte elements, whole 16-token tiles per block");
     static_assert(GQ <= 16, "one MFMA row per query");
@@ -83,10 +84,11 @@ __device__ __forceinline__ void prefix_mfma_body(const DecodeParams &P, const in
     const int h = block_index % H;
     const int rest = block_index / H;
 
-    // s: sequence whose table is walked; query c of this item is row q_row0 + c*q_row_step
-    // of P.q; tokens [0, t_hi) are visited; token t counts for query c iff t <= limit
-    int s, members, t_hi, t_lo, limit;
-    int64_t q_row0, q_row_step;
+    // Query c of the item is row q_row0 + c of P.q (and of P.out) and sees tokens
+    // 0 .. limit of its own sequence.  MULTI walks the block table of sequence s over
+    // tokens [0, t_hi); GROUP walks the tile list of the group that starts at s.
+    int s, members, nwork, t_hi = 0, t_lo = 0, limit = -1;
+    int64_t q_row0;
     if (MULTI) {
         const int qb = rest % P.q_blocks;
         s = rest / P.q_blocks;
@@ -99,22 +101,18 @@ __device__ __forceinline__ void prefix_mfma_body(const DecodeParams &P, const in
         t_lo = n - qlen + q0 + 1;            // tokens the first query of the item sees
         t_hi = t_lo + members - 1;           // tokens the last one sees
         if (t_hi > n) t_hi = n;
-        limit = c < members ? t_lo - 1 + c : -1;
+        if (c < members) limit = t_lo - 1 + c;
         q_row0 = qs + q0;
-        q_row_step = 1;
+        nwork = (t_hi + 15) / 16;            // 16-token tiles
     } else {
         if (rest >= P.ginfo[ginfo_shared_count(P.S)]) return;
         s = P.ginfo[ginfo_shared_list(P.S, rest)];   // a group is named by its first sequence
         members = P.ginfo[ginfo_group_size(P.S, s)];
-        t_hi = P.ginfo[ginfo_group_prefix(P.S, s)];
-        if (members < 2 || t_hi <= 0) return;
         if (members > GQ) members = GQ;
-        t_lo = t_hi;                          // every member sees every token of the prefix
-        limit = 0x7fffffff;
+        if (c < members) limit = P.context_lens[s + c] - 1;
         q_row0 = s;
-        q_row_step = 1;
+        nwork = P.ginfo[ginfo_tile_count(P.S, s)];   // tile-list entries (blocks)
     }
-    const int ntiles = (t_hi + 15) / 16;
 
     // Q^T as the B operand: lane l holds, for query l%16, the same byte ranges of the
     // query row that it will hold of each K row
@@ -124,8 +122,7 @@ __device__ __forceinline__ void prefix_mfma_body(const DecodeParams &P, const in
         qf[cc] = make_uint4(0, 0, 0, 0);
         if (c < members)
             qf[cc] = *reinterpret_cast<const uint4 *>(static_cast<const char *>(P.q) +
-                                                      ((q_row0 + c * q_row_step) * H + h) * ROW_BYTES +
-                                                      64 * cc + 16 * r);
+                                                      ((q_row0 + c) * H + h) * ROW_BYTES + 64 * cc + 16 * r);
     }
     float4_t O[8];
 #pragma unroll
@@ -133,13 +130,14 @@ __device__ __forceinline__ void prefix_mfma_body(const DecodeParams &P, const in
     float m = kNegBig, lsum = 0.f;
 
     const int32_t *__restrict__ table = P.block_tables + (int64_t)s * P.max_blocks;
+    const int2 *__restrict__ tiles = MULTI ? nullptr : P.tiles + (int64_t)s * P.max_blocks;
     const uint32_t k_lane_off = (uint32_t)((c / 4 + 4 * (c % 4)) * ROW_BYTES + 16 * r);
     const uint32_t v_lane_off = (uint32_t)lane * 16u;
 
-    for (int ti = w; ti < ntiles; ti += W) {
-        const int t0 = ti * 16;
-        const int pb = table[t0 / B];
-        const int64_t base = ((int64_t)pb * H + h) * TILE_BYTES + (int64_t)(t0 % B) * ROW_BYTES;
+    // one 16-token tile: first token t0 (position in the sequence), at byte `base` of
+    // the caches; rows at or past `rows` hold no token any query here sees;
+    // `mask`: queries that map this block; `check`: some entry may need masking
+    auto tile = [&](int64_t base, int t0, int rows, uint32_t mask, bool check) {
         uint4 kf[4], vf[4];
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc) kf[cc] = load16_stream(P.k_cache + base + k_lane_off + 64 * cc);
@@ -155,15 +153,14 @@ __device__ __forceinline__ void prefix_mfma_body(const DecodeParams &P, const in
         float x[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) x[v] = S[v] * P.scale_log2;
-        if (MULTI && t0 + 16 > t_lo) {
-            // the tile reaches past what the first query sees: apply the causal rule per
-            // (query, token), and clear V rows no query of the item sees (they may lie
-            // past the context and hold anything) - by select, never by multiplying
+        if (check) {
+            // by select, never by multiplying: rows past the stored tokens may hold anything
+            const bool mine = (mask >> c) & 1u;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int tok = t0 + r + 4 * v;
-                x[v] = tok <= limit ? x[v] : -INFINITY;
-                const bool unseen = tok >= t_hi;
+                const int row = r + 4 * v;
+                x[v] = (mine && t0 + row <= limit) ? x[v] : -INFINITY;
+                const bool unseen = row >= rows;
                 vf[v].x = unseen ? 0u : vf[v].x;
                 vf[v].y = unseen ? 0u : vf[v].y;
                 vf[v].z = unseen ? 0u : vf[v].z;
@@ -197,6 +194,33 @@ __device__ __forceinline__ void prefix_mfma_body(const DecodeParams &P, const in
             widen8<DT>(vv, vf[v]);
 #pragma unroll
             for (int e = 0; e < 8; ++e) O[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[v], vv[e], O[e], 0, 0, 0);
+        }
+    };
+
+    if (MULTI) {
+        for (int ti = w; ti < nwork; ti += W) {
+            const int t0 = ti * 16;
+            const int pb = table[t0 / B];
+            const int64_t base = ((int64_t)pb * H + h) * TILE_BYTES + (int64_t)(t0 % B) * ROW_BYTES;
+            // masking starts where the tile reaches past what the item's first query sees
+            tile(base, t0, t_hi - t0, 0xffffu, t0 + 16 > t_lo);
+        }
+    } else {
+        const uint32_t everyone = (1u << members) - 1u;
+        for (int ei = w; ei < nwork; ei += W) {
+            const int2 ent = tiles[ei];                        // wave-uniform: a scalar load
+            const uint32_t mask = (uint32_t)ent.y & 0xffu;
+            const int tokens = ((uint32_t)ent.y >> 8) & 0xffu; // tokens stored in the block
+            const int pos = ((uint32_t)ent.y >> 16) & 0x7fffu; // logical block index
+            const bool ragged = (uint32_t)ent.y >> 31;         // some member sees only part of the block
+            const int64_t base = ((int64_t)ent.x * H + h) * TILE_BYTES;
+#pragma unroll 1
+            for (int sub = 0; sub < SUBS; ++sub) {
+                if (sub * 16 >= tokens) break;
+                // a block that every member maps and sees in full needs no masking
+                const bool check = mask != everyone || ragged;
+                tile(base + (int64_t)sub * 16 * ROW_BYTES, pos * B + sub * 16, tokens - sub * 16, mask, check);
+            }
         }
     }
     lsum += __shfl_xor(lsum, 16);
@@ -233,18 +257,11 @@ __device__ __forceinline__ void prefix_mfma_body(const DecodeParams &P, const in
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[e] = __builtin_fmaf(sm_acc[i][j][8 * c + e], f, acc[e]);
         }
-        if (MULTI) {
-            const float inv = 1.0f / l;
+        // a member with an empty context has l = 0: its row is zero
+        const float inv = l > 0.f ? 1.0f / l : 0.f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] *= inv;
-            reinterpret_cast<uint4 *>(P.out)[((q_row0 + j) * H + h) * 16 + c] = Tr::pack(acc);
-        } else {
-            const int64_t slot = ((int64_t)(s + j) * H + h) * 2;
-            float *dst = P.ws_acc + slot * D + 8 * c;
-            *reinterpret_cast<float4 *>(dst) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-            *reinterpret_cast<float4 *>(dst + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
-            if (c == 0) *reinterpret_cast<float2 *>(P.ws_ml + slot * 2) = make_float2(M, l);
-        }
+        for (int e = 0; e < 8; ++e) acc[e] *= inv;
+        reinterpret_cast<uint4 *>(P.out)[((q_row0 + j) * H + h) * 16 + c] = Tr::pack(acc);
     }
 }
 
@@ -254,24 +271,26 @@ __device__ __forceinline__ void prefix_mfma_body(const DecodeParams &P, const in
 template <int DT, int B, int W>
 __global__ __launch_bounds__(W *kWave) void pa_decode_multi_kernel(const DecodeParams P)
 {
-    prefix_mfma_body<DT, B, W, 16, true>(P, (int)blockIdx.x);
+    mfma_body<DT, B, W, 16, true>(P, (int)blockIdx.x);
 }
 
-// Shared prefixes and private suffixes in one launch.  The first
-// P.prefix_blocks workgroups are shared-prefix items (group, head), the rest
-// are suffix items (sequence, head); the short prefix items start first and the
-// long suffix items fill the machine around them.
-template <int DT, int B, int WS, int WP>
-__global__ __launch_bounds__(WS *kWave) PA_OCC_ATTR_FUSED void pa_shared_fused_kernel(const DecodeParams P)
+// pa_decode_shared's main launch.  The first P.group_blocks workgroups are
+// (shared group, head) items on the matrix cores; the rest are (sequence, head)
+// items of the ordinary one-pass kernel for the sequences that share nothing
+// (members of a shared group end at once there).  Eight waves per workgroup:
+// two workgroups share a compute unit, so a group item's start-up latency is
+// covered by its neighbour's streaming.
+template <int DT, int B, int W>
+__global__ __launch_bounds__(W *kWave) void pa_shared_fused_kernel(const DecodeParams P)
 {
-    static_assert(WP == WS, "every wave of the workgroup takes part in either kind of item");
-    if ((int)blockIdx.x < P.prefix_blocks) {
-        prefix_mfma_body<DT, B, WP, kGroupMaxMfma, false>(P, (int)blockIdx.x);
+    if ((int)blockIdx.x < P.group_blocks) {
+        mfma_body<DT, B, W, kGroupMaxMfma, false>(P, (int)blockIdx.x);
     } else {
-        decode_body<DT, 128, B, WS, kChunksPerTripDevice, MODE_SUFFIX, 1>(P, (int)blockIdx.x - P.prefix_blocks);
+        const int idx = (int)blockIdx.x - P.group_blocks;
+        if (P.ginfo[ginfo_in_group(P.S, idx / P.H)]) return;
+        decode_body<DT, 128, B, W, kChunksPerTripDevice, MODE_SINGLE>(P, idx);
     }
 }
-
 
 } // namespace
 

@@ -78,7 +78,7 @@ def same_bits(t: torch.Tensor, a: np.ndarray, dtype: str) -> bool:
 def gpu_decode_shared(pa, dw: DeviceWorkload) -> torch.Tensor:
     w = dw.w
     out = torch.full_like(dw.q, float("nan"))
-    ws = torch.empty(pa.pa_decode_shared_workspace_bytes(w.num_seqs, w.num_heads, w.head_dim),
+    ws = torch.empty(pa.pa_decode_shared_workspace_bytes(w.num_seqs, w.num_heads, w.head_dim, w.max_blocks_per_seq),
                      dtype=torch.uint8, device="cuda")
     pa.pa_decode_shared(out, dw.q, dw.k_cache, dw.v_cache, dw.block_tables, dw.context_lens, w.block_size,
                         float(w.scale), w.max_context_len, ws)
