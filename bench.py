@@ -138,13 +138,17 @@ def cfg5_full_step(pa, W, np, torch, dev, steps):
            "cache_GB": 2 * L * NB * H * B * D * 2 / 1e9, "copy_pairs": int(len(w.copy_pairs)),
            "kv_GB_logical_per_step": L * w.kv_bytes_logical() / 1e9,
            "kv_GB_unique_per_step": L * w.kv_bytes_unique() / 1e9}
-    for name in ("plain", "shared"):
+    for name in ("plain", "shared", "shared_one_plan"):
         def step():
             pa.pa_copy_blocks(ks, vs, pairs)
+            if name == "shared_one_plan":    # the tables are the same for every layer of the step
+                pa.pa_shared_plan(bt, cl, H, D, B, NB, torch.bfloat16, mcl, ws)
             for l in range(L):
                 pa.pa_reshape_and_cache(k_new, v_new, ks[l], vs[l], slots)
                 if name == "shared":
                     pa.pa_decode_shared(out, q, ks[l], vs[l], bt, cl, B, float(w.scale), mcl, ws)
+                elif name == "shared_one_plan":
+                    pa.pa_decode_shared_planned(out, q, ks[l], vs[l], bt, cl, B, float(w.scale), mcl, ws)
                 else:
                     pa.pa_decode(out, q, ks[l], vs[l], bt, cl, B, float(w.scale), mcl, pa.PA_PARTITION_AUTO, ws)
         for _ in range(2):

@@ -138,6 +138,37 @@ size_t pa_decode_shared_workspace_bytes(int32_t num_seqs, int32_t num_heads, int
                                         int32_t max_blocks_per_seq);
 
 /*
+ * pa_shared_plan / pa_decode_shared_planned - pa_decode_shared in two steps.
+ * Every layer of a model uses the same block tables (Sec. 4.1, one table per
+ * sequence for all layers), so the grouping and the tile lists need building
+ * once per decoding step, not once per layer: pa_shared_plan enqueues the two
+ * preparation kernels and leaves the plan in `workspace`
+ * (pa_decode_shared_workspace_bytes(...) bytes, caller-owned);
+ * pa_decode_shared_planned enqueues only the decode launch and reads the plan.
+ * The plan is valid for exactly the block_tables, context_lens, num_seqs,
+ * max_blocks_per_seq and block_size it was built from, for as long as the
+ * caller leaves those arrays and the plan untouched; any change to them needs
+ * a new plan (a stale plan gives wrong results or out-of-range reads, unchecked).
+ * Plan and decode must be ordered on the device: same stream, or an event.
+ * pa_decode_shared(...) is pa_shared_plan(...) followed by
+ * pa_decode_shared_planned(...) on the same workspace.  For shapes that
+ * pa_decode_shared passes to pa_decode, the plan is empty and never read.
+ */
+pa_status pa_shared_plan(const int32_t *block_tables, int32_t max_blocks_per_seq,
+                         const int32_t *context_lens, int32_t num_seqs, int32_t num_heads,
+                         int32_t head_dim, int32_t block_size, int64_t num_blocks, pa_dtype dtype,
+                         int32_t max_context_len, void *workspace, size_t workspace_bytes,
+                         void *stream);
+
+pa_status pa_decode_shared_planned(void *out, const void *q, const void *k_cache,
+                                   const void *v_cache, const int32_t *block_tables,
+                                   int32_t max_blocks_per_seq, const int32_t *context_lens,
+                                   int32_t num_seqs, int32_t num_heads, int32_t head_dim,
+                                   int32_t block_size, int64_t num_blocks, pa_dtype dtype,
+                                   float scale, int32_t max_context_len, const void *plan,
+                                   size_t plan_bytes, void *stream);
+
+/*
  * pa_decode_multi - several query tokens per sequence over the paged cache:
  * the case where only the tail of a prompt has to be computed because its
  * prefix is already cached (Sec. 4.4, "Shared prefix"), or a few draft tokens

@@ -18,7 +18,7 @@ from .build import LIB
 PA_F32, PA_F16, PA_BF16 = 0, 1, 2
 PA_PARTITION_AUTO = -1
 
-EXPORTS = ("pa_decode", "pa_decode_workspace_bytes", "pa_decode_shared", "pa_decode_shared_workspace_bytes", "pa_decode_multi", "pa_reshape_and_cache", "pa_copy_blocks", "pa_swap_blocks",
+EXPORTS = ("pa_decode", "pa_decode_workspace_bytes", "pa_decode_shared", "pa_decode_shared_workspace_bytes", "pa_shared_plan", "pa_decode_shared_planned", "pa_decode_multi", "pa_reshape_and_cache", "pa_copy_blocks", "pa_swap_blocks",
            "pa_debug_validate", "pa_stream_read", "pa_status_string", "pa_version")
 
 _DT = {torch.float32: PA_F32, torch.float16: PA_F16, torch.bfloat16: PA_BF16}
@@ -50,6 +50,10 @@ def load_library() -> ctypes.CDLL:
     lib.pa_decode_shared.restype = ctypes.c_int
     lib.pa_decode_shared.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i64, ctypes.c_int,
                                      ctypes.c_float, i32, vp, sz, vp]
+    lib.pa_shared_plan.restype = ctypes.c_int
+    lib.pa_shared_plan.argtypes = [vp, i32, vp, i32, i32, i32, i32, i64, ctypes.c_int, i32, vp, sz, vp]
+    lib.pa_decode_shared_planned.restype = ctypes.c_int
+    lib.pa_decode_shared_planned.argtypes = lib.pa_decode_shared.argtypes
     lib.pa_decode_shared_workspace_bytes.restype = sz
     lib.pa_decode_shared_workspace_bytes.argtypes = [i32, i32, i32, i32]
     lib.pa_decode_multi.restype = ctypes.c_int
@@ -146,6 +150,38 @@ def pa_decode_shared(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, 
         block_tables.shape[1], _dev(context_lens, "context_lens", torch.int32), S, H, D, B, NB,
         _DT[q.dtype], float(scale), int(max_context_len), _dev(workspace, "workspace"),
         workspace.numel() * workspace.element_size(), _stream()))
+
+
+def pa_shared_plan(block_tables: torch.Tensor, context_lens: torch.Tensor, num_heads: int, head_dim: int,
+                   block_size: int, num_blocks: int, dtype: torch.dtype, max_context_len: int,
+                   workspace: torch.Tensor) -> None:
+    """Build pa_decode_shared's plan (groups and tile lists) for these tables in `workspace`."""
+    S = context_lens.shape[0]
+    if block_tables.dim() != 2 or block_tables.shape[0] != S:
+        raise ValueError("block_tables must be [S][MB], context_lens [S]")
+    _check(load_library().pa_shared_plan(
+        _dev(block_tables, "block_tables", torch.int32), block_tables.shape[1],
+        _dev(context_lens, "context_lens", torch.int32), S, int(num_heads), int(head_dim), int(block_size),
+        int(num_blocks), _DT[dtype], int(max_context_len), _dev(workspace, "workspace"),
+        workspace.numel() * workspace.element_size(), _stream()))
+
+
+def pa_decode_shared_planned(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                             block_tables: torch.Tensor, context_lens: torch.Tensor, block_size: int,
+                             scale: float, max_context_len: int, plan: torch.Tensor) -> None:
+    """pa_decode_shared's decode launch alone, reading a plan that pa_shared_plan built for the same tables."""
+    S, H, D = q.shape
+    NB, H2, B, D2 = k_cache.shape
+    if (H2, B, D2) != (H, block_size, D) or v_cache.shape != k_cache.shape or out.shape != q.shape:
+        raise ValueError("inconsistent shapes")
+    if block_tables.dim() != 2 or block_tables.shape[0] != S or context_lens.shape != (S,):
+        raise ValueError("block_tables must be [S][MB], context_lens [S]")
+    _check(load_library().pa_decode_shared_planned(
+        _dev(out, "out", q.dtype), _dev(q, "q"), _dev(k_cache, "k_cache", q.dtype),
+        _dev(v_cache, "v_cache", q.dtype), _dev(block_tables, "block_tables", torch.int32),
+        block_tables.shape[1], _dev(context_lens, "context_lens", torch.int32), S, H, D, B, NB,
+        _DT[q.dtype], float(scale), int(max_context_len), _dev(plan, "plan"),
+        plan.numel() * plan.element_size(), _stream()))
 
 
 def pa_decode_multi(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,

@@ -60,8 +60,11 @@ bool shape_supported(pa_dtype dt, int D, int B)
 struct DecodeArgs {
     DecodeParams p;
     int32_t waves;   // wavefronts per workgroup
+    int32_t steps;   // pa_decode_shared only: which of SHARED_PLAN, SHARED_DECODE to enqueue
     hipStream_t stream;
 };
+
+enum SharedSteps { SHARED_PLAN = 1, SHARED_DECODE = 2 };
 
 template <int DT, int D, int B, int W, int MODE>
 void launch_decode_kernel(const DecodeArgs &a, unsigned items)
@@ -79,15 +82,18 @@ void launch_shared(const DecodeArgs &a)
 {
     if constexpr (DT != PA_F32 && D == 128 && B % 16 == 0) {
         const unsigned S = (unsigned)a.p.S;
-        hipLaunchKernelGGL(find_groups_kernel, dim3(1), dim3(kGroupThreads), 0, a.stream, a.p.block_tables,
-                           a.p.max_blocks, a.p.context_lens, a.p.S, B, kGroupMaxMfma,
-                           const_cast<int32_t *>(a.p.ginfo));
         // a shared group has two or more members: at most S/2 groups
         const unsigned max_groups = (S + 1) / 2;
-        hipLaunchKernelGGL(build_tiles_kernel, dim3((max_groups + kTileWaves - 1) / kTileWaves),
-                           dim3(kTileWaves * kWave), 0, a.stream, a.p.block_tables, a.p.max_blocks,
-                           a.p.context_lens, a.p.S, B, const_cast<int32_t *>(a.p.ginfo),
-                           const_cast<int2 *>(a.p.tiles));
+        if (a.steps & SHARED_PLAN) {
+            hipLaunchKernelGGL(find_groups_kernel, dim3(1), dim3(kGroupThreads), 0, a.stream, a.p.block_tables,
+                               a.p.max_blocks, a.p.context_lens, a.p.S, B, kGroupMaxMfma,
+                               const_cast<int32_t *>(a.p.ginfo));
+            hipLaunchKernelGGL(build_tiles_kernel, dim3((max_groups + kTileWaves - 1) / kTileWaves),
+                               dim3(kTileWaves * kWave), 0, a.stream, a.p.block_tables, a.p.max_blocks,
+                               a.p.context_lens, a.p.S, B, const_cast<int32_t *>(a.p.ginfo),
+                               const_cast<int2 *>(a.p.tiles));
+        }
+        if (!(a.steps & SHARED_DECODE)) return;
         DecodeArgs f = a;
         f.p.group_blocks = (int32_t)(max_groups * (unsigned)a.p.H);
         const unsigned blocks = (unsigned)f.p.group_blocks + S * (unsigned)a.p.H;
@@ -322,12 +328,13 @@ size_t pa_decode_shared_workspace_bytes(int32_t num_seqs, int32_t num_heads, int
     return ginfo_bytes(num_seqs) + (size_t)num_seqs * max_blocks_per_seq * sizeof(int2);
 }
 
-pa_status pa_decode_shared(void *out, const void *q, const void *k_cache, const void *v_cache,
-                           const int32_t *block_tables, int32_t max_blocks_per_seq,
-                           const int32_t *context_lens, int32_t num_seqs, int32_t num_heads,
-                           int32_t head_dim, int32_t block_size, int64_t num_blocks, pa_dtype dtype,
-                           float scale, int32_t max_context_len, void *workspace,
-                           size_t workspace_bytes, void *stream)
+static pa_status decode_shared_steps(int steps, void *out, const void *q, const void *k_cache,
+                                     const void *v_cache, const int32_t *block_tables,
+                                     int32_t max_blocks_per_seq, const int32_t *context_lens,
+                                     int32_t num_seqs, int32_t num_heads, int32_t head_dim,
+                                     int32_t block_size, int64_t num_blocks, pa_dtype dtype, float scale,
+                                     int32_t max_context_len, void *workspace, size_t workspace_bytes,
+                                     void *stream)
 {
     if (num_seqs < 0 || num_heads <= 0 || head_dim <= 0 || block_size <= 0 || num_blocks <= 0 ||
         max_blocks_per_seq <= 0 || max_context_len < 0)
@@ -335,14 +342,20 @@ pa_status pa_decode_shared(void *out, const void *q, const void *k_cache, const 
     if (!shape_supported(dtype, head_dim, block_size)) return PA_ERR_UNSUPPORTED;
     if ((int64_t)max_context_len > (int64_t)max_blocks_per_seq * block_size) return PA_ERR_SHAPE;
     if (num_seqs == 0) return PA_OK;
-    if (!out || !q || !k_cache || !v_cache || !block_tables || !context_lens) return PA_ERR_NULL;
-    if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return PA_ERR_ALIGN;
+    if (!block_tables || !context_lens) return PA_ERR_NULL;
+    if ((steps & SHARED_DECODE) && (!out || !q || !k_cache || !v_cache)) return PA_ERR_NULL;
+    if ((steps & SHARED_DECODE) &&
+        (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)))
+        return PA_ERR_ALIGN;
     if ((int64_t)num_seqs * num_heads > (int64_t)0x7fffffff / 64) return PA_ERR_SHAPE;
-    if (!shared_on_matrix_cores(dtype, head_dim, block_size, max_blocks_per_seq))
-        // no several-query kernel for this shape: the plain one-pass kernel gives the same result
+    if (!shared_on_matrix_cores(dtype, head_dim, block_size, max_blocks_per_seq)) {
+        // no several-query kernel for this shape: nothing to plan, and the plain one-pass
+        // kernel gives the same result
+        if (!(steps & SHARED_DECODE)) return PA_OK;
         return pa_decode(out, q, k_cache, v_cache, block_tables, max_blocks_per_seq, context_lens, num_seqs,
                          num_heads, head_dim, block_size, num_blocks, dtype, scale, max_context_len, 0,
                          nullptr, 0, stream);
+    }
     const size_t need = pa_decode_shared_workspace_bytes(num_seqs, num_heads, head_dim, max_blocks_per_seq);
     if (!workspace || workspace_bytes < need) return PA_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PA_ERR_ALIGN;
@@ -352,11 +365,46 @@ pa_status pa_decode_shared(void *out, const void *q, const void *k_cache, const 
     fill_common(a, out, q, k_cache, v_cache, block_tables, max_blocks_per_seq, context_lens, num_seqs,
                 num_heads, scale, stream);
     a.p.max_parts = 1;
+    a.steps = steps;
     a.waves = waves_for(max_context_len, chunk_tokens(dtype, head_dim, block_size));
     a.p.ginfo = static_cast<const int32_t *>(workspace);
     a.p.tiles = reinterpret_cast<const int2 *>(static_cast<const char *>(workspace) + ginfo_bytes(num_seqs));
     if (!dispatch_decode(a, dtype, head_dim, block_size, PLAN_SHARED)) return PA_ERR_UNSUPPORTED;
     return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
+}
+
+pa_status pa_decode_shared(void *out, const void *q, const void *k_cache, const void *v_cache,
+                           const int32_t *block_tables, int32_t max_blocks_per_seq,
+                           const int32_t *context_lens, int32_t num_seqs, int32_t num_heads,
+                           int32_t head_dim, int32_t block_size, int64_t num_blocks, pa_dtype dtype,
+                           float scale, int32_t max_context_len, void *workspace,
+                           size_t workspace_bytes, void *stream)
+{
+    return decode_shared_steps(SHARED_PLAN | SHARED_DECODE, out, q, k_cache, v_cache, block_tables,
+                               max_blocks_per_seq, context_lens, num_seqs, num_heads, head_dim, block_size,
+                               num_blocks, dtype, scale, max_context_len, workspace, workspace_bytes, stream);
+}
+
+pa_status pa_shared_plan(const int32_t *block_tables, int32_t max_blocks_per_seq,
+                         const int32_t *context_lens, int32_t num_seqs, int32_t num_heads,
+                         int32_t head_dim, int32_t block_size, int64_t num_blocks, pa_dtype dtype,
+                         int32_t max_context_len, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return decode_shared_steps(SHARED_PLAN, nullptr, nullptr, nullptr, nullptr, block_tables,
+                               max_blocks_per_seq, context_lens, num_seqs, num_heads, head_dim, block_size,
+                               num_blocks, dtype, 0.f, max_context_len, workspace, workspace_bytes, stream);
+}
+
+pa_status pa_decode_shared_planned(void *out, const void *q, const void *k_cache, const void *v_cache,
+                                   const int32_t *block_tables, int32_t max_blocks_per_seq,
+                                   const int32_t *context_lens, int32_t num_seqs, int32_t num_heads,
+                                   int32_t head_dim, int32_t block_size, int64_t num_blocks,
+                                   pa_dtype dtype, float scale, int32_t max_context_len,
+                                   const void *plan, size_t plan_bytes, void *stream)
+{
+    return decode_shared_steps(SHARED_DECODE, out, q, k_cache, v_cache, block_tables, max_blocks_per_seq,
+                               context_lens, num_seqs, num_heads, head_dim, block_size, num_blocks, dtype,
+                               scale, max_context_len, const_cast<void *>(plan), plan_bytes, stream);
 }
 
 pa_status pa_decode_multi(void *out, const void *q, const void *k_cache, const void *v_cache,

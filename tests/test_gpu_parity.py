@@ -164,6 +164,49 @@ def test_shared_decode_fully_shared_and_mixed(pa):
         print(dtype, run_and_compare(pa, w, partitions=(SHARED, 0)))
 
 
+def test_shared_plan_reused_across_layers(pa):
+    # one plan per decoding step: three "layers" (different cache contents and queries, same
+    # tables) decoded from one plan give the bits of the one-call path and match the oracle;
+    # also a shape that has no several-query kernel (the plan is empty, the decode still right)
+    for w in (W.config5(num_seqs=14, H=2, min_len=60, max_len=500),
+              W.config3(num_groups=3, H=2, prompt_median=40, prompt_cap=100, max_out=30)):
+        S, H, D, B = w.num_seqs, w.num_heads, w.head_dim, w.block_size
+        plan = torch.empty(pa.pa_decode_shared_workspace_bytes(S, H, D, w.max_blocks_per_seq),
+                           dtype=torch.uint8, device="cuda")
+        layers = []
+        for layer in range(3):
+            v = W.make_values(w, seed=w.seed + 100 * layer)
+            dw = DeviceWorkload(w, v)
+            gpu_cache_ops(pa, dw)
+            layers.append((v, dw))
+        dw0 = layers[0][1]
+        tdt = dw0.q.dtype
+        pa.pa_shared_plan(dw0.block_tables, dw0.context_lens, H, D, B, w.num_blocks, tdt, w.max_context_len, plan)
+        for v, dw in layers:
+            out = torch.full_like(dw.q, float("nan"))
+            pa.pa_decode_shared_planned(out, dw.q, dw.k_cache, dw.v_cache, dw0.block_tables, dw0.context_lens, B,
+                                        float(w.scale), w.max_context_len, plan)
+            torch.cuda.synchronize()
+            assert same_bits(out, to_np(gpu_decode_shared(pa, dw), w.dtype), w.dtype)
+            kc, vc = oracle_cache_ops(w, v)
+            ref = oracle.decode(v.q, kc, vc, w.block_tables, w.context_lens, w.scale, w.dtype)
+            err = float(np.abs(out_to_f64(out, w.dtype) - ref).max())
+            assert err <= TOL[w.dtype], err
+    w = W.config1()
+    v = W.make_values(w)
+    dw = DeviceWorkload(w, v)
+    gpu_cache_ops(pa, dw)
+    plan = torch.empty(max(16, pa.pa_decode_shared_workspace_bytes(w.num_seqs, w.num_heads, w.head_dim,
+                                                                    w.max_blocks_per_seq)), dtype=torch.uint8, device="cuda")
+    pa.pa_shared_plan(dw.block_tables, dw.context_lens, w.num_heads, w.head_dim, w.block_size, w.num_blocks,
+                      dw.q.dtype, w.max_context_len, plan)
+    out = torch.full_like(dw.q, float("nan"))
+    pa.pa_decode_shared_planned(out, dw.q, dw.k_cache, dw.v_cache, dw.block_tables, dw.context_lens, w.block_size,
+                                float(w.scale), w.max_context_len, plan)
+    torch.cuda.synchronize()
+    assert same_bits(out, to_np(gpu_decode(pa, dw, 0), w.dtype), w.dtype)
+
+
 # ---------------------------------------------------------------------------
 # several query tokens per sequence (causal), on the matrix cores
 # ---------------------------------------------------------------------------
