@@ -61,6 +61,7 @@ struct DecodeArgs {
     DecodeParams p;
     int32_t waves;   // wavefronts per workgroup
     int32_t steps;   // pa_decode_shared only: which of SHARED_PLAN, SHARED_DECODE to enqueue
+    bool long_lists; // pa_decode_shared only: contexts beyond 2048 tokens
     hipStream_t stream;
 };
 
@@ -97,7 +98,12 @@ void launch_shared(const DecodeArgs &a)
         DecodeArgs f = a;
         f.p.group_blocks = (int32_t)(max_groups * (unsigned)a.p.H);
         const unsigned blocks = (unsigned)f.p.group_blocks + S * (unsigned)a.p.H;
-        if (a.waves >= 8)
+        // A group item walks up to (members x context / 16) tiles.  Past 2048 tokens of context
+        // that chain, at eight waves, is a large part of the whole launch, and the last items
+        // to start decide when the launch ends: sixteen waves per item halve it.
+        if (a.waves >= 16 && a.long_lists)
+            hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 16>), dim3(blocks), dim3(16 * kWave), 0, a.stream, f.p);
+        else if (a.waves >= 8)
             hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 8>), dim3(blocks), dim3(8 * kWave), 0, a.stream, f.p);
         else
             hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 4>), dim3(blocks), dim3(4 * kWave), 0, a.stream, f.p);
@@ -366,6 +372,7 @@ static pa_status decode_shared_steps(int steps, void *out, const void *q, const 
                 num_heads, scale, stream);
     a.p.max_parts = 1;
     a.steps = steps;
+    a.long_lists = max_context_len > 2048;
     a.waves = waves_for(max_context_len, chunk_tokens(dtype, head_dim, block_size));
     a.p.ginfo = static_cast<const int32_t *>(workspace);
     a.p.tiles = reinterpret_cast<const int2 *>(static_cast<const char *>(workspace) + ginfo_bytes(num_seqs));

@@ -16,10 +16,14 @@ namespace {
 //   MULTI  the last q_len tokens of one sequence as causal queries.
 // Wave w takes tiles w, w+W, ...  Per 16-token tile:
 //   S^T = K Q^T   8 x v_mfma_f32_16x16x16 (f16 or bf16 operands, fp32 result):
-//                 A rows are tokens, B columns are queries.  Lane l supplies
-//                 row l%16; each of its four 16-byte loads feeds two MFMAs,
-//                 with the same (arbitrary but consistent) assignment of head
-//                 dimensions to contraction slots on the Q side.
+//                 A rows are tokens, B columns are queries.  The K tile is
+//                 loaded like V, 1 KiB per instruction (a lane-per-row load
+//                 would fetch half cache lines and runs about 15% slower),
+//                 and turned into MFMA rows through the wave's own LDS
+//                 region: lane l reads back 4 x 16 bytes of row l%16, each
+//                 feeding two MFMAs, with the same (arbitrary but consistent)
+//                 assignment of head dimensions to contraction slots on the
+//                 Q side.
 //   softmax       the result leaves lane l with query l%16 and four tokens;
 //                 entries of queries that do not map the block, or of tokens a
 //                 query does not see, are set to -inf by select; the running
@@ -31,7 +35,7 @@ namespace {
 //                 dims 8*(l%16)+e; output column l%16 of MFMA e is dim
 //                 8*(l%16)+e).  fp32 operands keep P exact; the fp32 matrix
 //                 rate is still about three times what the HBM stream needs.
-// K rows are loaded in the order token(i) = i/4 + 4*(i%4) so that result
+// K rows are read back in the order token(i) = i/4 + 4*(i%4) so that result
 // register v of lane l belongs to token l/16 + 4v, the token of V fragment v
 // in that lane: P never moves between lanes and V needs no transpose.
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
@@ -131,8 +135,19 @@ __device__ __forceinline__ void mfma_body(const DecodeParams &P, const int block
 
     const int32_t *__restrict__ table = P.block_tables + (int64_t)s * P.max_blocks;
     const int2 *__restrict__ tiles = MULTI ? nullptr : P.tiles + (int64_t)s * P.max_blocks;
-    const uint32_t k_lane_off = (uint32_t)((c / 4 + 4 * (c % 4)) * ROW_BYTES + 16 * r);
     const uint32_t v_lane_off = (uint32_t)lane * 16u;
+
+    // One region of LDS per wave.  While the wave streams it is the staging area of its K
+    // tile: K rows arrive by the same coalesced load as V (lane l: token l/16 + 4j, bytes
+    // 16*(l%16) of the row) and are read back as MFMA rows (lane l: token row of l%16).
+    // Rows are padded by 16 bytes so that the 16 rows one read touches fall in different
+    // banks.  When the wave is done the region holds its partial result for the merge.
+    constexpr int K_ROW_PAD = ROW_BYTES + 16;
+    constexpr int REGION = (16 * K_ROW_PAD > GQ * D * 4) ? 16 * K_ROW_PAD : GQ * D * 4;
+    __shared__ __align__(16) char sm_region[W][REGION];
+    char *const kst = sm_region[w];
+    const uint32_t kst_write = (uint32_t)(r * K_ROW_PAD + 16 * c);                      // + 4j rows
+    const uint32_t kst_read = (uint32_t)((c / 4 + 4 * (c % 4)) * K_ROW_PAD + 16 * r);   // + 64cc bytes
 
     // one 16-token tile: first token t0 (position in the sequence), at byte `base` of
     // the caches; rows at or past `rows` hold no token any query here sees;
@@ -140,9 +155,18 @@ __device__ __forceinline__ void mfma_body(const DecodeParams &P, const int block
     auto tile = [&](int64_t base, int t0, int rows, uint32_t mask, bool check) {
         uint4 kf[4], vf[4];
 #pragma unroll
-        for (int cc = 0; cc < 4; ++cc) kf[cc] = load16_stream(P.k_cache + base + k_lane_off + 64 * cc);
+        for (int j = 0; j < 4; ++j) kf[j] = load16_stream(P.k_cache + base + v_lane_off + 1024 * j);
 #pragma unroll
         for (int v = 0; v < 4; ++v) vf[v] = load16_stream(P.v_cache + base + v_lane_off + 1024 * v);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) *reinterpret_cast<uint4 *>(kst + kst_write + 4 * j * K_ROW_PAD) = kf[j];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) kf[cc] = *reinterpret_cast<const uint4 *>(kst + kst_read + 64 * cc);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
 
         float4_t S = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -227,14 +251,14 @@ __device__ __forceinline__ void mfma_body(const DecodeParams &P, const int block
     lsum += __shfl_xor(lsum, 32);
 
     // merge the waves: per query, its 128 accumulators sit in the 16 lanes r = query/4
-    __shared__ float sm_acc[W][GQ][D];
+    auto sm_acc = [&](int wave) { return reinterpret_cast<float(*)[D]>(sm_region[wave]); };
     __shared__ float sm_m[W][GQ], sm_l[W][GQ];
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         const int qi = 4 * r + v;
         if (qi < members) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sm_acc[w][qi][8 * c + e] = O[e][v];
+            for (int e = 0; e < 8; ++e) sm_acc(w)[qi][8 * c + e] = O[e][v];
         }
     }
     if (r == 0 && c < members) {
@@ -255,7 +279,7 @@ __device__ __forceinline__ void mfma_body(const DecodeParams &P, const int block
             const float f = __builtin_amdgcn_exp2f(sm_m[i][j] - M);
             l = __builtin_fmaf(sm_l[i][j], f, l);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] = __builtin_fmaf(sm_acc[i][j][8 * c + e], f, acc[e]);
+            for (int e = 0; e < 8; ++e) acc[e] = __builtin_fmaf(sm_acc(i)[j][8 * c + e], f, acc[e]);
         }
         // a member with an empty context has l = 0: its row is zero
         const float inv = l > 0.f ? 1.0f / l : 0.f;

@@ -110,6 +110,10 @@ def test_shared_decode_beam_groups_of_six(pa):
     # groups larger than the kernel's query slots are split; beams share 55% of their blocks
     w = W.config5(num_seqs=20, H=3, min_len=100, max_len=900)
     print(run_and_compare(pa, w, partitions=(SHARED, 0)))
+    # contexts past 2048 tokens: group items run with sixteen waves
+    w = W.config5(seed=5007, num_seqs=8, H=2, min_len=1800, max_len=2400)
+    assert w.max_context_len > 2048
+    print(run_and_compare(pa, w, partitions=(SHARED,)))
 
 
 def test_shared_decode_without_sharing(pa):
