@@ -55,6 +55,9 @@ def parse():
                          "layer cache write + decode")
     ap.add_argument("--multi-query", action="store_true",
                     help="instead of the step benchmark: pa_decode_multi at the OPT-13B shape for several q_len")
+    ap.add_argument("--paging-overhead", action="store_true",
+                    help="instead of the step benchmark: pa_decode over randomly placed blocks against the same "
+                         "sequences stored contiguously (the axis of the paper's kernel microbenchmark, Sec. 7.1)")
     ap.add_argument("--cache-ops", action="store_true",
                     help="instead of the step benchmark: pa_reshape_and_cache and pa_copy_blocks at several sizes")
     return ap.parse_args()
@@ -112,6 +115,44 @@ def block_size_sweep(pa, W, np, torch, dev):
                      "pool_blocks": w.num_blocks})
         del kc, vc
     print(json.dumps({"metric": "pa_decode_block_size_sweep", "workload": "OPT-13B shape, 64 seq, ctx U{1..2048}, fp16",
+                      "rows": rows}))
+
+
+def paging_overhead(pa, W, np, torch, dev):
+    """The paper's kernel microbenchmark (Sec. 7.1) compares its kernel over scattered blocks with an
+    attention kernel over contiguous K/V.  Here: the same kernel, the same 64 sequences and bytes, with
+    (a) blocks placed at random in a pool 1.2x the need, (b) every sequence's blocks consecutive in the
+    pool (what a contiguous per-sequence cache looks like through a block table), for B = 16 and 128.
+    The table walk itself is part of both; the difference is what non-contiguity costs on this device."""
+    rng = np.random.default_rng(2000)
+    lens = rng.integers(1, 2049, size=64)
+    H, D = 40, 128
+    rows = []
+    for B in (16, 128):
+        w = W.independent_sequences("opt13b_B%d" % B, "f16", H, D, B, lens, 2001)
+        nblk = (lens + B - 1) // B
+        contiguous = np.full_like(w.block_tables, -1)
+        start = 0
+        for s_, nb in enumerate(nblk):
+            contiguous[s_, :nb] = np.arange(start, start + nb)
+            start += int(nb)
+        kc = torch.randn((w.num_blocks, H, B, D), dtype=torch.float16, device=dev)
+        vc = torch.randn_like(kc)
+        q = torch.randn((64, H, D), dtype=torch.float16, device=dev)
+        out = torch.empty_like(q)
+        cl = torch.from_numpy(w.context_lens).to(dev)
+        row = {"block_size": B}
+        for name, table in (("scattered", w.block_tables), ("contiguous", contiguous)):
+            bt = torch.from_numpy(np.ascontiguousarray(table)).to(dev)
+            us = min(_time_us(lambda: pa.pa_decode(out, q, kc, vc, bt, cl, B, float(w.scale), w.max_context_len,
+                                                   0, None), 100, torch) for _ in range(3))
+            row[name + "_us"] = us
+            row[name + "_GBps"] = w.kv_bytes_logical() / us / 1e3
+        row["scattered_over_contiguous"] = row["scattered_us"] / row["contiguous_us"]
+        rows.append(row)
+        del kc, vc
+    print(json.dumps({"metric": "pa_decode_paging_overhead",
+                      "workload": "OPT-13B shape, 64 seq, ctx U{1..2048}, fp16, best of 3 x 100 launches",
                       "rows": rows}))
 
 
@@ -262,6 +303,8 @@ def main():
         return block_size_sweep(pa, W, np, torch, dev)
     if args.cache_ops:
         return cache_ops(pa, np, torch, dev)
+    if args.paging_overhead:
+        return paging_overhead(pa, W, np, torch, dev)
     if args.multi_query:
         return multi_query(pa, W, np, torch, dev)
     if args.cfg5_full_step:
