@@ -84,3 +84,68 @@ def test_argument_errors_need_no_gpu(lib):
 
     assert lib.pa_stream_read(None, 1024, p, None) == 1
     assert lib.pa_stream_read(p, 1000, p, None) == 2
+
+
+def test_argument_errors_of_the_wider_entry_points(lib):
+    buf = ctypes.create_string_buffer(64 + 16)
+    p = (ctypes.addressof(buf) + 15) & ~15       # aligned, non-null, never dereferenced
+    f32, f16 = 0, 1
+
+    def shared(fn=None, **kw):
+        a = dict(out=p, q=p, k=p, v=p, bt=p, mb=8, cl=p, S=2, H=2, D=128, B=16, NB=4, dt=f16, scale=1.0,
+                 mcl=100, ws=p, wsb=1 << 20)
+        a.update(kw)
+        return (fn or lib.pa_decode_shared)(a["out"], a["q"], a["k"], a["v"], a["bt"], a["mb"], a["cl"], a["S"],
+                                            a["H"], a["D"], a["B"], a["NB"], a["dt"], a["scale"], a["mcl"],
+                                            a["ws"], a["wsb"], None)
+
+    need = lib.pa_decode_shared_workspace_bytes(2, 2, 128, 8)
+    assert need == ((5 * 2 + 4) * 4 + 15) // 16 * 16 + 2 * 8 * 8    # group table + one (id, info) pair per table entry
+    for fn in (lib.pa_decode_shared, lib.pa_decode_shared_planned):
+        assert shared(fn, S=0) == 0
+        assert shared(fn, k=None) == 1
+        assert shared(fn, mb=0) == 2
+        assert shared(fn, mcl=8 * 16 + 1) == 2
+        assert shared(fn, D=96) == 3
+        assert shared(fn, v=p + 8) == 4
+        assert shared(fn, ws=None) == 5
+        assert shared(fn, wsb=need - 1) == 5
+        assert shared(fn, ws=p + 4) == 4
+
+    def plan(**kw):
+        a = dict(bt=p, mb=8, cl=p, S=2, H=2, D=128, B=16, NB=4, dt=f16, mcl=100, ws=p, wsb=1 << 20)
+        a.update(kw)
+        return lib.pa_shared_plan(a["bt"], a["mb"], a["cl"], a["S"], a["H"], a["D"], a["B"], a["NB"], a["dt"],
+                                  a["mcl"], a["ws"], a["wsb"], None)
+
+    assert plan(S=0) == 0
+    assert plan(bt=None) == 1
+    assert plan(B=0) == 2
+    assert plan(dt=7) == 3
+    assert plan(wsb=need - 1) == 5
+    assert plan(dt=f32, D=64) == 0               # no several-query kernel for this shape: nothing to plan
+
+    def multi(**kw):
+        a = dict(out=p, q=p, k=p, v=p, bt=p, mb=8, cl=p, qs=p, S=2, mq=4, H=2, D=128, B=16, NB=4, dt=f16,
+                 scale=1.0, mcl=100)
+        a.update(kw)
+        return lib.pa_decode_multi(a["out"], a["q"], a["k"], a["v"], a["bt"], a["mb"], a["cl"], a["qs"], a["S"],
+                                   a["mq"], a["H"], a["D"], a["B"], a["NB"], a["dt"], a["scale"], a["mcl"], None)
+
+    assert multi(S=0) == 0
+    assert multi(mq=0) == 0                      # no query rows: nothing to do
+    assert multi(qs=None) == 1
+    assert multi(mq=-1) == 2
+    assert multi(dt=f32) == 3                    # two-byte types only
+    assert multi(D=64) == 3
+    assert multi(B=8) == 3
+    assert multi(q=p + 2) == 4
+
+    arr = (ctypes.c_void_p * 1)(p)
+    swap = lambda sk=arr, L=1, n=2, nbs=4, nbd=4, pairs=p: lib.pa_swap_blocks(sk, arr, arr, arr, L, pairs, n, 2, 128,
+                                                                               16, nbs, nbd, f16, None)
+    assert swap(n=0) == 0
+    assert swap(sk=None) == 1
+    assert swap(pairs=None) == 1
+    assert swap(L=0) == 2
+    assert swap(nbd=0) == 2
