@@ -212,10 +212,15 @@ int auto_partition(int S, int H, int max_context_len)
     return ps >= max_context_len ? 0 : (int)ps;
 }
 
-template <int DT>
-bool launch_multi(const DecodeArgs &a, int B, unsigned blocks)
+// Waves per (sequence, 16 queries, head) item.  Each wave holds 16 query rows of partial results
+// (8 KiB of LDS).  With few queries per sequence the grid is small and the items are pure
+// streaming: eight waves read faster (195 against 202 us at the OPT-13B shape, q_len <= 4).
+// With many query blocks per sequence the items re-read K/V out of L2 and are bound by the
+// matrix pipe; four waves, four items per compute unit, do better there (2.07 against 2.51 ms
+// at q_len 256).
+template <int DT, int W>
+bool launch_multi_w(const DecodeArgs &a, int B, unsigned blocks)
 {
-    constexpr int W = 4;   // 16 query rows of partial results per wave: four waves fill 32 KiB of LDS
     switch (B) {
     case 16: hipLaunchKernelGGL((pa_decode_multi_kernel<DT, 16, W>), dim3(blocks), dim3(W * kWave), 0, a.stream, a.p); return true;
     case 32: hipLaunchKernelGGL((pa_decode_multi_kernel<DT, 32, W>), dim3(blocks), dim3(W * kWave), 0, a.stream, a.p); return true;
@@ -223,6 +228,12 @@ bool launch_multi(const DecodeArgs &a, int B, unsigned blocks)
     case 128: hipLaunchKernelGGL((pa_decode_multi_kernel<DT, 128, W>), dim3(blocks), dim3(W * kWave), 0, a.stream, a.p); return true;
     }
     return false;
+}
+
+template <int DT>
+bool launch_multi(const DecodeArgs &a, int B, unsigned blocks, int max_q_len)
+{
+    return max_q_len <= 8 ? launch_multi_w<DT, 8>(a, B, blocks) : launch_multi_w<DT, 4>(a, B, blocks);
 }
 
 void fill_common(DecodeArgs &a, void *out, const void *q, const void *k_cache, const void *v_cache,
@@ -440,8 +451,8 @@ pa_status pa_decode_multi(void *out, const void *q, const void *k_cache, const v
                 num_heads, scale, stream);
     a.p.q_start = q_start;
     a.p.q_blocks = (int32_t)q_blocks;
-    const bool ok = dtype == PA_F16 ? launch_multi<PA_F16>(a, block_size, (unsigned)blocks)
-                                    : launch_multi<PA_BF16>(a, block_size, (unsigned)blocks);
+    const bool ok = dtype == PA_F16 ? launch_multi<PA_F16>(a, block_size, (unsigned)blocks, max_q_len)
+                                    : launch_multi<PA_BF16>(a, block_size, (unsigned)blocks, max_q_len);
     if (!ok) return PA_ERR_UNSUPPORTED;
     return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
 }

@@ -292,8 +292,11 @@ __device__ __forceinline__ void mfma_body(const DecodeParams &P, const int block
 // Several query tokens per sequence (the tail of a prompt over an already cached
 // prefix, Sec. 4.4 "shared prefix"; or draft tokens to verify): grid =
 // (sequence, block of 16 queries, head).
+// (at least four waves per SIMD, i.e. at most 128 VGPRs: otherwise the compiler takes 136 and a
+// third of the residency is lost)
 template <int DT, int B, int W>
-__global__ __launch_bounds__(W *kWave) void pa_decode_multi_kernel(const DecodeParams P)
+__global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) void pa_decode_multi_kernel(
+    const DecodeParams P)
 {
     mfma_body<DT, B, W, 16, true>(P, (int)blockIdx.x);
 }

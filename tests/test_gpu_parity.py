@@ -245,6 +245,10 @@ def test_multi_query_decode(pa):
     for dtype in ("f16", "bf16"):
         print(dtype, multi_case(pa, dtype, lens, q_lens))
     print("B=32", multi_case(pa, "bf16", lens, q_lens, H=2, B=32))
+    # a few queries per sequence (draft tokens): the eight-wave variant
+    few = [min(n, k) for n, k in zip(lens, [1, 2, 8, 4, 8, 5, 7, 1, 8, 3, 0, 6, 2, 8])]
+    for dtype in ("f16", "bf16"):
+        print(dtype, "q_len <= 8", multi_case(pa, dtype, lens, few, seed=43))
     print("B=64", multi_case(pa, "f16", [500, 130, 64], [20, 130, 1], H=2, B=64))
 
 
