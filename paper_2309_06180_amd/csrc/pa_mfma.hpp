@@ -308,7 +308,8 @@ __global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))
 // two workgroups share a compute unit, so a group item's start-up latency is
 // covered by its neighbour's streaming.
 template <int DT, int B, int W>
-__global__ __launch_bounds__(W *kWave) void pa_shared_fused_kernel(const DecodeParams P)
+__global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) void pa_shared_fused_kernel(
+    const DecodeParams P)
 {
     if ((int)blockIdx.x < P.group_blocks) {
         mfma_body<DT, B, W, kGroupMaxMfma, false>(P, (int)blockIdx.x);
