@@ -116,6 +116,13 @@ def test_shared_decode_beam_groups_of_six(pa):
     print(run_and_compare(pa, w, partitions=(SHARED,)))
 
 
+def test_shared_decode_large_batch(pa):
+    # more sequences than the group discovery keeps in LDS (2048) and than it has threads (1024)
+    w = W.config3(seed=3011, num_groups=640, H=1, prompt_median=30, prompt_cap=70, max_out=24)
+    assert w.num_seqs == 2560
+    print(run_and_compare(pa, w, partitions=(SHARED, 0)))
+
+
 def test_shared_decode_without_sharing(pa):
     # nothing in common: every sequence is a group of one and only the suffix path runs
     for dtype, D in (("f16", 128), ("bf16", 128), ("f32", 64)):
