@@ -98,6 +98,32 @@ def test_every_workgroup_width(pa, max_len):
         print(dtype, run_and_compare(pa, w, partitions=(0, 64, 512, 1024)))
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_seeded_random_cases(pa, seed):
+    # a seeded walk through the supported set: workload kind, type, head size, block size, heads,
+    # lengths and partition sizes all drawn at random; every case through one-pass, split, auto and
+    # the sharing-aware call
+    rng = np.random.default_rng(9000 + seed)
+    dtype = ["f16", "bf16", "f32"][rng.integers(0, 3)]
+    D = [64, 128][rng.integers(0, 2)]
+    B = [8, 16, 32, 64, 128][rng.integers(0, 5)]
+    H = int(rng.integers(1, 6))
+    kind = ["independent", "sampling", "beam"][rng.integers(0, 3)]
+    top = int(rng.integers(1, 900))
+    if kind == "independent":
+        lens = rng.integers(0, top + 1, size=int(rng.integers(1, 20)))
+        w = W.independent_sequences("rand", dtype, H, D, B, lens, seed=seed)
+    elif kind == "sampling":
+        w = W.config3(seed=seed, num_groups=int(rng.integers(1, 6)), group=int(rng.integers(2, 6)), H=H, D=D, B=B,
+                      dtype=dtype, prompt_median=max(2, top // 4), prompt_cap=top + 2, max_out=int(rng.integers(1, 120)))
+    else:
+        w = W.config5(seed=seed, num_seqs=int(rng.integers(2, 20)), width=int(rng.integers(2, 10)), H=H, D=D, B=B,
+                      dtype=dtype, min_len=max(2, top // 3), max_len=top + 2)
+    ps = int(rng.integers(1, 9)) * max(B, 32)
+    print(kind, dtype, D, B, H, w.num_seqs, w.max_context_len, ps,
+          run_and_compare(pa, w, partitions=(0, ps, pa.PA_PARTITION_AUTO, SHARED)))
+
+
 # ---------------------------------------------------------------------------
 # shared-prefix decode: same oracle, same tolerance
 # ---------------------------------------------------------------------------
