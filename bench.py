@@ -58,6 +58,9 @@ def parse():
     ap.add_argument("--paging-overhead", action="store_true",
                     help="instead of the step benchmark: pa_decode over randomly placed blocks against the same "
                          "sequences stored contiguously (the axis of the paper's kernel microbenchmark, Sec. 7.1)")
+    ap.add_argument("--short-batches", action="store_true",
+                    help="instead of the step benchmark: pa_decode on large batches of short sequences (the regime "
+                         "of the paper's second trace, whose sequences are a few dozen tokens long)")
     ap.add_argument("--cache-ops", action="store_true",
                     help="instead of the step benchmark: pa_reshape_and_cache and pa_copy_blocks at several sizes")
     return ap.parse_args()
@@ -153,6 +156,33 @@ def paging_overhead(pa, W, np, torch, dev):
         del kc, vc
     print(json.dumps({"metric": "pa_decode_paging_overhead",
                       "workload": "OPT-13B shape, 64 seq, ctx U{1..2048}, fp16, best of 3 x 100 launches",
+                      "rows": rows}))
+
+
+def short_batches(pa, W, np, torch, dev):
+    """Many short sequences per batch (Sec. 6.1: the second trace has prompts and outputs several times
+    shorter than the first, and is served at batch sizes in the hundreds): per (sequence, head) only a
+    few blocks, so launch planning and per-item overhead show.  OPT-13B shape, fp16, B = 16."""
+    H, D, B = 40, 128, 16
+    rows = []
+    for S, top in ((128, 128), (256, 64), (256, 128), (256, 256), (512, 128), (1024, 128)):
+        rng = np.random.default_rng(S + top)
+        lens = rng.integers(1, top + 1, size=S)
+        w = W.independent_sequences("short", "f16", H, D, B, lens, 1)
+        kc = torch.randn((w.num_blocks, H, B, D), dtype=torch.float16, device=dev)
+        vc = torch.randn_like(kc)
+        q = torch.randn((S, H, D), dtype=torch.float16, device=dev)
+        out = torch.empty_like(q)
+        bt = torch.from_numpy(w.block_tables).to(dev)
+        cl = torch.from_numpy(w.context_lens).to(dev)
+        us = _time_us(lambda: pa.pa_decode(out, q, kc, vc, bt, cl, B, float(w.scale), w.max_context_len, 0, None),
+                      100, torch)
+        kv = w.kv_bytes_logical()
+        rows.append({"num_seqs": S, "max_len": top, "us": us, "kv_MB": kv / 1e6, "kv_GBps": kv / us / 1e3,
+                     "frac_of_peak": kv / us / 1e3 / HBM_PEAK_GBPS, "query_tokens_per_s": S / us * 1e6,
+                     "fits_infinity_cache": bool(kv < 256e6)})
+        del kc, vc
+    print(json.dumps({"metric": "pa_decode_short_batches", "workload": "OPT-13B shape, fp16, B=16, ctx U{1..max_len}",
                       "rows": rows}))
 
 
@@ -305,6 +335,8 @@ def main():
         return cache_ops(pa, np, torch, dev)
     if args.paging_overhead:
         return paging_overhead(pa, W, np, torch, dev)
+    if args.short_batches:
+        return short_batches(pa, W, np, torch, dev)
     if args.multi_query:
         return multi_query(pa, W, np, torch, dev)
     if args.cfg5_full_step:
