@@ -61,6 +61,9 @@ def parse():
     ap.add_argument("--short-batches", action="store_true",
                     help="instead of the step benchmark: pa_decode on large batches of short sequences (the regime "
                          "of the paper's second trace, whose sequences are a few dozen tokens long)")
+    ap.add_argument("--shared-prefix", action="store_true",
+                    help="instead of the step benchmark: one prefix shared by every sequence of the batch "
+                         "(Sec. 4.4 / 6.4), pa_decode against pa_decode_shared")
     ap.add_argument("--cache-ops", action="store_true",
                     help="instead of the step benchmark: pa_reshape_and_cache and pa_copy_blocks at several sizes")
     return ap.parse_args()
@@ -184,6 +187,34 @@ def short_batches(pa, W, np, torch, dev):
         del kc, vc
     print(json.dumps({"metric": "pa_decode_short_batches", "workload": "OPT-13B shape, fp16, B=16, ctx U{1..max_len}",
                       "rows": rows}))
+
+
+def shared_prefix(pa, W, np, torch, dev):
+    """Sec. 4.4 "Shared prefix" / Sec. 6.4: every request starts with the same prefix (the paper uses
+    one example of 80 tokens and five examples of 341 tokens), stored once and mapped by all; each
+    request adds its own tokens (here U{1..128}).  256 sequences, OPT-13B-like shape, fp16, B = 16."""
+    S, H, D, B = 256, 40, 128, 16
+    rows = []
+    for prefix in (80, 341, 1024):
+        w = W.config3(seed=6000 + prefix, num_groups=1, group=S, H=H, D=D, B=B, prompt_median=prefix,
+                      prompt_sigma=1e-9, prompt_cap=prefix, max_out=128)
+        kc = torch.randn((w.num_blocks, H, B, D), dtype=torch.float16, device=dev)
+        vc = torch.randn_like(kc)
+        q = torch.randn((S, H, D), dtype=torch.float16, device=dev)
+        out = torch.empty_like(q)
+        bt = torch.from_numpy(w.block_tables).to(dev)
+        cl = torch.from_numpy(w.context_lens).to(dev)
+        ws = torch.empty(pa.pa_decode_shared_workspace_bytes(S, H, D, w.max_blocks_per_seq), dtype=torch.uint8,
+                         device=dev)
+        mcl = w.max_context_len
+        plain = _time_us(lambda: pa.pa_decode(out, q, kc, vc, bt, cl, B, float(w.scale), mcl, 0, None), 100, torch)
+        sh = _time_us(lambda: pa.pa_decode_shared(out, q, kc, vc, bt, cl, B, float(w.scale), mcl, ws), 100, torch)
+        rows.append({"prefix_tokens": prefix, "kv_MB_logical": w.kv_bytes_logical() / 1e6,
+                     "kv_MB_unique": w.kv_bytes_unique() / 1e6, "pa_decode_us": plain, "pa_decode_shared_us": sh,
+                     "query_tokens_per_s_plain": S / plain * 1e6, "query_tokens_per_s_shared": S / sh * 1e6})
+        del kc, vc
+    print(json.dumps({"metric": "pa_decode_shared_prefix", "workload": "256 seq share one prefix, + U{1..128} own "
+                      "tokens each, 40 heads x 128, fp16, B=16", "rows": rows}))
 
 
 def cfg5_full_step(pa, W, np, torch, dev, steps):
@@ -337,6 +368,8 @@ def main():
         return paging_overhead(pa, W, np, torch, dev)
     if args.short_batches:
         return short_batches(pa, W, np, torch, dev)
+    if args.shared_prefix:
+        return shared_prefix(pa, W, np, torch, dev)
     if args.multi_query:
         return multi_query(pa, W, np, torch, dev)
     if args.cfg5_full_step:
