@@ -63,8 +63,15 @@ __device__ __host__ __forceinline__ size_t ginfo_words(int S) { return 5 * (size
 // lengths, two resident workgroups each run at half speed and stretch the end
 // of the launch by more than their overlap gains.
 #define PA_OCC_ATTR __attribute__((amdgpu_waves_per_eu(W == 16 ? 4 : 1, W == 16 ? 7 : 8)))
-template <int DT, int D, int B, int W, int U, int MODE>
-__device__ __forceinline__ void decode_body(const DecodeParams &P, const int block_index)
+
+// Tokens [t_begin, t_end) of sequence s (t_begin < t_end, t_begin a multiple of the chunk size)
+// against head h: on return wave 0's lanes with g == 0 hold the range's running maximum m (log2
+// units), exp-sum l and unnormalised weighted V sum acc[] for their EPL dimensions; other
+// lanes hold nothing useful.  Every wave of the workgroup must call it (it synchronises).
+template <int DT, int D, int B, int W, int U>
+__device__ __forceinline__ void decode_range(const DecodeParams &P, const int s, const int h, const int t_begin,
+                                             const int t_end, float &m, float &l,
+                                             float (&acc)[Traits<DT>::EPL])
 {
     using Tr = Traits<DT>;
     constexpr int E = Tr::E, EPL = Tr::EPL;
@@ -83,29 +90,12 @@ __device__ __forceinline__ void decode_body(const DecodeParams &P, const int blo
     const uint32_t lane16 = (uint32_t)lane * 16u;
     const int H = P.H;
 
-    int item = block_index;
-    const int h = item % H;
-    item /= H;
-    const int part = MODE == MODE_PART ? item % P.max_parts : 0;
-    const int s = MODE == MODE_PART ? item / P.max_parts : item;
-
-    const int n = P.context_lens[s];
-    const int t_begin = MODE == MODE_PART ? part * P.partition_size : 0;
-    const int t_end = MODE == MODE_PART ? (t_begin + P.partition_size < n ? t_begin + P.partition_size : n) : n;
-    if (t_begin >= t_end) {
-        if (MODE == MODE_SINGLE && w == 0 && g == 0) {
-            // empty context: zero row
-            reinterpret_cast<uint4 *>(P.out)[((int64_t)s * H + h) * LPT + c] = make_uint4(0, 0, 0, 0);
-        }
-        return;
-    }
-
     const uint4 qf = reinterpret_cast<const uint4 *>(P.q)[((int64_t)s * H + h) * LPT + c];
     const int32_t *__restrict__ table = P.block_tables + (int64_t)s * P.max_blocks;
     const int nchunks = (t_end - t_begin + CT - 1) / CT;
 
-    float m = kNegBig, l = 0.f;
-    float acc[EPL];
+    m = kNegBig;
+    l = 0.f;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
 
@@ -245,7 +235,42 @@ __device__ __forceinline__ void decode_body(const DecodeParams &P, const int blo
         }
         m = M;
     }
-    if (g != 0) return;
+}
+
+// One work item of the decode kernel: a (sequence, head) over its whole context, or over one
+// fixed-size partition of it.
+template <int DT, int D, int B, int W, int U, int MODE>
+__device__ __forceinline__ void decode_body(const DecodeParams &P, const int block_index)
+{
+    using Tr = Traits<DT>;
+    constexpr int EPL = Tr::EPL;
+    constexpr int LPT = D * Tr::E / 16;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int g = lane / LPT;
+    const int c = lane % LPT;
+    const int H = P.H;
+
+    int item = block_index;
+    const int h = item % H;
+    item /= H;
+    const int part = MODE == MODE_PART ? item % P.max_parts : 0;
+    const int s = MODE == MODE_PART ? item / P.max_parts : item;
+
+    const int n = P.context_lens[s];
+    const int t_begin = MODE == MODE_PART ? part * P.partition_size : 0;
+    const int t_end = MODE == MODE_PART ? (t_begin + P.partition_size < n ? t_begin + P.partition_size : n) : n;
+    if (t_begin >= t_end) {
+        if (MODE == MODE_SINGLE && w == 0 && g == 0) {
+            // empty context: zero row
+            reinterpret_cast<uint4 *>(P.out)[((int64_t)s * H + h) * LPT + c] = make_uint4(0, 0, 0, 0);
+        }
+        return;
+    }
+
+    float m, l, acc[EPL];
+    decode_range<DT, D, B, W, U>(P, s, h, t_begin, t_end, m, l, acc);
+    if (w != 0 || g != 0) return;
 
     if (MODE == MODE_SINGLE) {
         const float inv = 1.0f / l;
