@@ -48,15 +48,18 @@ struct DecodeParams {
 // Layout of the group table of pa_decode_shared, arrays of S int32 entries:
 // in_group[s] (1 if s belongs to a group of two or more), group_size[s] (members
 // of the group that starts at sequence s, 0 if none starts there), tile_count[s]
-// (entries of that group's tile list), adj[s] (scratch of the discovery), the
-// compact list of the first sequences of shared groups, and its length.
+// (entries of that group's tile list), adj[s] (scratch of the discovery),
+// own_start[s] (for a member of a group: the token position from which it reads its
+// blocks itself; everything before is on the group's tile list), the compact list of
+// the first sequences of shared groups, and its length.
 __device__ __host__ __forceinline__ int ginfo_in_group(int S, int s) { (void)S; return s; }
 __device__ __host__ __forceinline__ int ginfo_group_size(int S, int s) { return S + s; }
 __device__ __host__ __forceinline__ int ginfo_tile_count(int S, int s) { return 2 * S + s; }
 __device__ __host__ __forceinline__ int ginfo_adj(int S, int s) { return 3 * S + s; }
-__device__ __host__ __forceinline__ int ginfo_shared_list(int S, int i) { return 4 * S + i; }
-__device__ __host__ __forceinline__ int ginfo_shared_count(int S) { return 5 * S; }
-__device__ __host__ __forceinline__ size_t ginfo_words(int S) { return 5 * (size_t)S + 4; }
+__device__ __host__ __forceinline__ int ginfo_own_start(int S, int s) { return 4 * S + s; }
+__device__ __host__ __forceinline__ int ginfo_shared_list(int S, int i) { return 5 * S + i; }
+__device__ __host__ __forceinline__ int ginfo_shared_count(int S) { return 6 * S; }
+__device__ __host__ __forceinline__ size_t ginfo_words(int S) { return 6 * (size_t)S + 4; }
 
 // A sixteen-wave workgroup is kept alone on its compute unit (at most 7 waves
 // per SIMD, so a second one does not fit): measured on batches of mixed
@@ -64,13 +67,14 @@ __device__ __host__ __forceinline__ size_t ginfo_words(int S) { return 5 * (size
 // of the launch by more than their overlap gains.
 #define PA_OCC_ATTR __attribute__((amdgpu_waves_per_eu(W == 16 ? 4 : 1, W == 16 ? 7 : 8)))
 
-// Tokens [t_begin, t_end) of sequence s (t_begin < t_end, t_begin a multiple of the chunk size)
-// against head h: on return wave 0's lanes with g == 0 hold the range's running maximum m (log2
-// units), exp-sum l and unnormalised weighted V sum acc[] for their EPL dimensions; other
-// lanes hold nothing useful.  Every wave of the workgroup must call it (it synchronises).
-template <int DT, int D, int B, int W, int U>
-__device__ __forceinline__ void decode_range(const DecodeParams &P, const int s, const int h, const int t_begin,
-                                             const int t_end, float &m, float &l,
+// One wave's share of tokens [t_begin, t_end) of sequence s against head h (t_begin < t_end,
+// t_begin a multiple of the chunk size): the wave takes chunks wv, wv + nw, ... of the range.
+// On return its lanes with g == 0 hold the running maximum m (log2 units), exp-sum l and
+// unnormalised weighted V sum acc[] of those chunks for their EPL dimensions (m = -big, l = 0
+// if it had none).
+template <int DT, int D, int B, int U>
+__device__ __forceinline__ void stream_range(const DecodeParams &P, const int s, const int h, const int t_begin,
+                                             const int t_end, const int wv, const int nw, float &m, float &l,
                                              float (&acc)[Traits<DT>::EPL])
 {
     using Tr = Traits<DT>;
@@ -84,7 +88,6 @@ __device__ __forceinline__ void decode_range(const DecodeParams &P, const int s,
     static_assert(LPT >= 8 && LPT <= 32 && B % TPL == 0 && B % CT == 0 && LPC >= 1, "shape");
 
     const int lane = threadIdx.x & (kWave - 1);
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int g = lane / LPT;
     const int c = lane % LPT;
     const uint32_t lane16 = (uint32_t)lane * 16u;
@@ -169,18 +172,18 @@ __device__ __forceinline__ void decode_range(const DecodeParams &P, const int s,
     // one chunk at a time with masking.  Latency is hidden by the other waves
     // resident on the SIMD.
     {
-        int ci = w;
-        for (; ci + (U - 1) * W <= nchunks - 2; ci += U * W) {
+        int ci = wv;
+        for (; ci + (U - 1) * nw <= nchunks - 2; ci += U * nw) {
             Chunk ck[U];
             int pb[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) pb[u] = block_of(ci + u * W);
+            for (int u = 0; u < U; ++u) pb[u] = block_of(ci + u * nw);
 #pragma unroll
-            for (int u = 0; u < U; ++u) issue(ck[u], ci + u * W, pb[u]);
+            for (int u = 0; u < U; ++u) issue(ck[u], ci + u * nw, pb[u]);
 #pragma unroll
-            for (int u = 0; u < U; ++u) consume(ck[u], ci + u * W, full);
+            for (int u = 0; u < U; ++u) consume(ck[u], ci + u * nw, full);
         }
-        for (; ci < nchunks; ci += W) {
+        for (; ci < nchunks; ci += nw) {
             Chunk ck;
             issue(ck, ci, block_of(ci));
             consume(ck, ci, masked);
@@ -204,6 +207,25 @@ __device__ __forceinline__ void decode_range(const DecodeParams &P, const int s,
         }
         m = M;
     }
+
+}
+
+// Tokens [t_begin, t_end) of sequence s against head h with all W waves of the workgroup: on
+// return wave 0's lanes with g == 0 hold m, l and acc[] of the whole range; other lanes hold
+// nothing useful.  Every wave of the workgroup must call it (it synchronises).
+template <int DT, int D, int B, int W, int U>
+__device__ __forceinline__ void decode_range(const DecodeParams &P, const int s, const int h, const int t_begin,
+                                             const int t_end, float &m, float &l,
+                                             float (&acc)[Traits<DT>::EPL])
+{
+    using Tr = Traits<DT>;
+    constexpr int EPL = Tr::EPL;
+    constexpr int LPT = D * Tr::E / 16;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int g = lane / LPT;
+    const int c = lane % LPT;
+    stream_range<DT, D, B, U>(P, s, h, t_begin, t_end, w, W, m, l, acc);
 
     // merge the W waves of the workgroup through LDS
     if (W > 1) {

@@ -127,17 +127,22 @@ __global__ __launch_bounds__(kGroupThreads) void find_groups_kernel(
     if (threadIdx.x == 0) ginfo[ginfo_shared_count(S)] = running;
 }
 
-// Tile list of a shared group: every distinct physical block its members map,
-// once, with the set of members that map it.  Forked sequences share a block
-// only at the same logical position, so the members' tables are compared
-// position by position: lane i of the group's wavefront looks at logical block
-// base+i of all members, keeps the first member of every set of equal ids and
-// records (block id, member mask, tokens stored in the block, position).  A
-// wave-wide prefix sum of the per-position counts places the entries, in
-// position order, at tiles[first_sequence * max_blocks ...].
+// Tile list of a shared group.  Forked sequences share a block only at the same
+// logical position, so the members' tables are compared position by position.
+// For member j, run[j] is the number of leading positions at which its block is
+// also mapped by another member: those blocks go on the group's list, once each,
+// with the set of members that take them from the list; from position run[j]
+// on, member j reads its blocks itself (own_start = run[j] * block_size tokens).
+// Lane i of the group's wavefront looks at logical block base+i of all members,
+// keeps the first member of every set of equal ids and records (block id,
+// member mask, tokens stored in the block, position); a wave-wide prefix sum of
+// the per-position counts places the entries, in position order, at
+// tiles[first_sequence * max_blocks ...].  Nothing about the sharing pattern is
+// assumed: a block mapped by several members past somebody's run is simply read
+// by each of them.
 //   entry.x = physical block,
 //   entry.y = mask | tokens << 8 | position << 16 | ragged << 31, where ragged says that
-//             some member mapping the block sees fewer tokens of it than the block holds
+//             some member in the mask sees fewer tokens of the block than it holds
 constexpr int kTileWaves = 4;
 __global__ __launch_bounds__(kTileWaves *kWave) void build_tiles_kernel(
     const int32_t *__restrict__ block_tables, int32_t max_blocks,
@@ -150,41 +155,68 @@ __global__ __launch_bounds__(kTileWaves *kWave) void build_tiles_kernel(
     const int start = ginfo[ginfo_shared_list(S, gi)];
     const int G = ginfo[ginfo_group_size(S, start)];
     int n[kGroupMaxMfma], nb[kGroupMaxMfma], maxnb = 0;
+    int run[kGroupMaxMfma];      // closed runs: their length; open ones: -1
 #pragma unroll
     for (int j = 0; j < kGroupMaxMfma; ++j) {
         n[j] = j < G ? context_lens[start + j] : 0;
         nb[j] = (n[j] + block_size - 1) / block_size;
         maxnb = nb[j] > maxnb ? nb[j] : maxnb;
+        run[j] = j < G ? -1 : 0;
     }
     int2 *out = tiles + (int64_t)start * max_blocks;
     int placed = 0;
-    for (int base = 0; base < maxnb; base += kWave) {
+    bool any_open = true;
+    for (int base = 0; base < maxnb && any_open; base += kWave) {
         const int i = base + lane;
         int id[kGroupMaxMfma];
 #pragma unroll
         for (int j = 0; j < kGroupMaxMfma; ++j)
             id[j] = i < nb[j] ? block_tables[(int64_t)(start + j) * max_blocks + i] : -1 - j;
         uint32_t firsts = 0, mask[kGroupMaxMfma];
-        int nmax[kGroupMaxMfma], nmin[kGroupMaxMfma];
 #pragma unroll
         for (int j = 0; j < kGroupMaxMfma; ++j) {
             mask[j] = 0;
-            nmax[j] = 0;
-            nmin[j] = 0x7fffffff;
             bool first = i < nb[j];
 #pragma unroll
             for (int j2 = 0; j2 < kGroupMaxMfma; ++j2) {
-                const bool same = i < nb[j2] && id[j2] == id[j];
-                if (same) {
+                if (i < nb[j2] && id[j2] == id[j]) {
                     mask[j] |= 1u << j2;
-                    nmax[j] = n[j2] > nmax[j] ? n[j2] : nmax[j];
-                    nmin[j] = n[j2] < nmin[j] ? n[j2] : nmin[j];
                     if (j2 < j) first = false;
                 }
             }
             if (first) firsts |= 1u << j;
         }
-        const int count = __builtin_popcount(firsts);
+        // runs: member j stays on the list up to the first position where nobody shares its block
+        uint32_t on_list = 0;    // this lane's position is inside the run of these members
+        any_open = false;
+#pragma unroll
+        for (int j = 0; j < kGroupMaxMfma; ++j) {
+            if (run[j] >= 0) continue;                       // closed in an earlier batch (uniform)
+            const unsigned long long stop = __ballot(__builtin_popcount(mask[j]) < 2);
+            const int len = stop ? (int)__builtin_ctzll(stop) : kWave;
+            if (lane < len) on_list |= 1u << j;
+            if (stop)
+                run[j] = base + len;
+            else
+                any_open = true;
+        }
+        uint32_t emit = 0;
+        int nmax[kGroupMaxMfma], nmin[kGroupMaxMfma];
+#pragma unroll
+        for (int j = 0; j < kGroupMaxMfma; ++j) {
+            mask[j] &= on_list;
+            nmax[j] = 0;
+            nmin[j] = 0x7fffffff;
+#pragma unroll
+            for (int j2 = 0; j2 < kGroupMaxMfma; ++j2) {
+                if ((mask[j] >> j2) & 1u) {
+                    nmax[j] = n[j2] > nmax[j] ? n[j2] : nmax[j];
+                    nmin[j] = n[j2] < nmin[j] ? n[j2] : nmin[j];
+                }
+            }
+            if (((firsts >> j) & 1u) && mask[j]) emit |= 1u << j;
+        }
+        const int count = __builtin_popcount(emit);
         int incl = count;   // inclusive prefix sum over lanes
 #pragma unroll
         for (int d = 1; d < kWave; d <<= 1) {
@@ -195,17 +227,25 @@ __global__ __launch_bounds__(kTileWaves *kWave) void build_tiles_kernel(
         const int at = placed + incl - count;
 #pragma unroll
         for (int j = 0; j < kGroupMaxMfma; ++j) {
-            if ((firsts >> j) & 1u) {
+            if ((emit >> j) & 1u) {
                 int tokens = nmax[j] - i * block_size;
                 tokens = tokens < block_size ? tokens : block_size;
                 const uint32_t ragged = nmin[j] < (i + 1) * block_size ? 1u : 0u;
-                out[at + __builtin_popcount(firsts & ((1u << j) - 1u))] =
+                out[at + __builtin_popcount(emit & ((1u << j) - 1u))] =
                     make_int2(id[j], (int)(mask[j] | ((uint32_t)tokens << 8) | ((uint32_t)i << 16) | (ragged << 31)));
             }
         }
         placed += total;
     }
-    if (lane == 0) ginfo[ginfo_tile_count(S, start)] = placed;
+    if (lane == 0) {
+        ginfo[ginfo_tile_count(S, start)] = placed;
+#pragma unroll
+        for (int j = 0; j < kGroupMaxMfma; ++j) {
+            // a run still open when the positions ran out covers the member's whole table
+            const int blocks = run[j] >= 0 ? run[j] : nb[j];
+            if (j < G) ginfo[ginfo_own_start(S, start + j)] = blocks * block_size;
+        }
+    }
 }
 
 } // namespace

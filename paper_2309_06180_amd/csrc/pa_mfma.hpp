@@ -71,8 +71,11 @@ __device__ __forceinline__ void widen8(float (&f)[8], const uint4 &v)
     }
 }
 
+// GROUP leaves, for member j, the unnormalised result of the tiles on the list in LDS
+// (part_acc[j][128], part_m[j] in log2 units, part_l[j]); MULTI writes the finished rows.
 template <int DT, int B, int W, int GQ, bool MULTI>
-__device__ __forceinline__ void mfma_body(const DecodeParams &P, const int block_index)
+__device__ __forceinline__ void mfma_body(const DecodeParams &P, const int block_index, float (*part_acc)[128],
+                                          float *part_m, float *part_l)
 {
     using Tr = Traits<DT>;
     constexpr int D = 128, ROW_BYTES = 256, SUBS = B / 16;
@@ -266,26 +269,36 @@ __device__ __forceinline__ void mfma_body(const DecodeParams &P, const int block
         sm_l[w][c] = lsum;
     }
     __syncthreads();
-    if (w != 0 || r != 0) return;
-    for (int j = 0; j < members; ++j) {
-        float M = sm_m[0][j];
+    if (w == 0 && r == 0) {
+        for (int j = 0; j < members; ++j) {
+            float M = sm_m[0][j];
 #pragma unroll
-        for (int i = 1; i < W; ++i) M = fmaxf(M, sm_m[i][j]);
-        float l = 0.f, acc[8];
+            for (int i = 1; i < W; ++i) M = fmaxf(M, sm_m[i][j]);
+            float l = 0.f, acc[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+            for (int e = 0; e < 8; ++e) acc[e] = 0.f;
 #pragma unroll 2
-        for (int i = 0; i < W; ++i) {
-            const float f = __builtin_amdgcn_exp2f(sm_m[i][j] - M);
-            l = __builtin_fmaf(sm_l[i][j], f, l);
+            for (int i = 0; i < W; ++i) {
+                const float f = __builtin_amdgcn_exp2f(sm_m[i][j] - M);
+                l = __builtin_fmaf(sm_l[i][j], f, l);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] = __builtin_fmaf(sm_acc(i)[j][8 * c + e], f, acc[e]);
+                for (int e = 0; e < 8; ++e) acc[e] = __builtin_fmaf(sm_acc(i)[j][8 * c + e], f, acc[e]);
+            }
+            if (MULTI) {
+                // a query with an empty context has l = 0: its row is zero
+                const float inv = l > 0.f ? 1.0f / l : 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] *= inv;
+                reinterpret_cast<uint4 *>(P.out)[((q_row0 + j) * H + h) * 16 + c] = Tr::pack(acc);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) part_acc[j][8 * c + e] = acc[e];
+                if (c == 0) {
+                    part_m[j] = M;
+                    part_l[j] = l;
+                }
+            }
         }
-        // a member with an empty context has l = 0: its row is zero
-        const float inv = l > 0.f ? 1.0f / l : 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] *= inv;
-        reinterpret_cast<uint4 *>(P.out)[((q_row0 + j) * H + h) * 16 + c] = Tr::pack(acc);
     }
 }
 
@@ -298,21 +311,97 @@ template <int DT, int B, int W>
 __global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) void pa_decode_multi_kernel(
     const DecodeParams P)
 {
-    mfma_body<DT, B, W, 16, true>(P, (int)blockIdx.x);
+    mfma_body<DT, B, W, 16, true>(P, (int)blockIdx.x, nullptr, nullptr, nullptr);
+}
+
+// One (shared group, head) item of pa_decode_shared.  The blocks that members have in common
+// are on the group's tile list and go through the matrix cores once for everybody who maps
+// them.  From its own_start on, a member's remaining blocks are its own business: the waves
+// of the workgroup are dealt out among the members (W / members waves each, at least one;
+// more members than waves take several rounds) and stream them with the ordinary
+// single-query pass.  A member's results - tile list, and one per wave - are merged by the
+// log-sum-exp rule and the finished row is written: nothing partial leaves the workgroup.
+template <int DT, int B, int W>
+__device__ __forceinline__ void group_item(const DecodeParams &P, const int block_index)
+{
+    using Tr = Traits<DT>;
+    constexpr int EPL = Tr::EPL, LPT = 16, D = 128;
+    __shared__ float part_acc[kGroupMaxMfma][D];
+    __shared__ float part_m[kGroupMaxMfma], part_l[kGroupMaxMfma];
+    __shared__ float own_acc[W][D];
+    __shared__ float own_m[W], own_l[W];
+    const int H = P.H;
+    const int h = block_index % H;
+    const int rest = block_index / H;
+    if (rest >= P.ginfo[ginfo_shared_count(P.S)]) return;
+    const int s0 = P.ginfo[ginfo_shared_list(P.S, rest)];
+    int members = P.ginfo[ginfo_group_size(P.S, s0)];
+    if (members > kGroupMaxMfma) members = kGroupMaxMfma;
+
+    mfma_body<DT, B, W, kGroupMaxMfma, false>(P, block_index, part_acc, part_m, part_l);
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int g = lane / LPT;
+    const int c = lane % LPT;
+    const int per = W / members > 0 ? W / members : 1;   // waves per member
+    const int slots = W / per;                           // members served at a time
+    const int slot = w % slots, k = w / slots;           // this wave: k-th wave of the slot's member
+    for (int first = 0; first < members; first += slots) {
+        const int j = first + slot;
+        const bool active = k < per && j < members;
+        float m = kNegBig, l = 0.f, acc[EPL];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+        int sq = s0, n = 0;
+        if (active) {
+            sq = s0 + j;
+            n = P.context_lens[sq];
+            const int own = P.ginfo[ginfo_own_start(P.S, sq)];
+            if (own < n) stream_range<DT, D, B, kChunksPerTripDevice>(P, sq, h, own, n, k, per, m, l, acc);
+        }
+        if (g == 0) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) own_acc[w][c * EPL + e] = acc[e];
+            if (c == 0) {
+                own_m[w] = m;
+                own_l[w] = l;
+            }
+        }
+        __syncthreads();   // also orders the tile-list results of wave 0 before their readers
+        if (active && k == 0 && g == 0) {
+            float M = part_m[j];
+            for (int i = 0; i < per; ++i) M = fmaxf(M, own_m[slot + i * slots]);
+            const float f_list = __builtin_amdgcn_exp2f(part_m[j] - M);
+            l = part_l[j] * f_list;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] = part_acc[j][c * EPL + e] * f_list;
+            for (int i = 0; i < per; ++i) {
+                const int wi = slot + i * slots;
+                const float f = __builtin_amdgcn_exp2f(own_m[wi] - M);
+                l = __builtin_fmaf(own_l[wi], f, l);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[e] = __builtin_fmaf(own_acc[wi][c * EPL + e], f, acc[e]);
+            }
+            const float inv = l > 0.f ? 1.0f / l : 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] *= inv;
+            reinterpret_cast<uint4 *>(P.out)[((int64_t)sq * H + h) * LPT + c] = Tr::pack(acc);
+        }
+        __syncthreads();   // the next round reuses own_acc
+    }
 }
 
 // pa_decode_shared's main launch.  The first P.group_blocks workgroups are
-// (shared group, head) items on the matrix cores; the rest are (sequence, head)
-// items of the ordinary one-pass kernel for the sequences that share nothing
-// (members of a shared group end at once there).  Eight waves per workgroup:
-// two workgroups share a compute unit, so a group item's start-up latency is
-// covered by its neighbour's streaming.
+// (shared group, head) items; the rest are (sequence, head) items of the ordinary
+// one-pass kernel for the sequences that share nothing (members of a shared group
+// end at once there).
 template <int DT, int B, int W>
 __global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) void pa_shared_fused_kernel(
     const DecodeParams P)
 {
     if ((int)blockIdx.x < P.group_blocks) {
-        mfma_body<DT, B, W, kGroupMaxMfma, false>(P, (int)blockIdx.x);
+        group_item<DT, B, W>(P, (int)blockIdx.x);
     } else {
         const int idx = (int)blockIdx.x - P.group_blocks;
         if (P.ginfo[ginfo_in_group(P.S, idx / P.H)]) return;
