@@ -113,12 +113,13 @@ size_t pa_decode_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t he
  * common logical blocks to the same physical blocks).  Same arguments, same
  * result as pa_decode; the difference is traffic.  On the device, the library
  * compares the block tables of consecutive sequences, groups up to 8
- * neighbours that have leading blocks in common, lists every distinct
- * physical block of a group once with the set of members that map it, and
- * runs each group through a kernel that applies every K/V tile it loads to
- * all members mapping it (on the matrix cores) and writes the members'
- * finished output rows.  Sequences that share nothing go through the
- * ordinary one-pass kernel in the same launch.
+ * neighbours that have leading blocks in common, and lists the blocks that
+ * members share (each once, with the set of members that map it).  One
+ * workgroup per (group, head) applies every listed K/V tile to all members
+ * mapping it (on the matrix cores), streams each member's remaining, unshared
+ * blocks with the ordinary single-query pass, merges the two and writes the
+ * members' finished output rows.  Sequences that share nothing go through
+ * the ordinary one-pass kernel in the same launch.
  *
  * Callers should place sequences that were forked from one another next to
  * each other in the batch; any order is correct, only sharing between
