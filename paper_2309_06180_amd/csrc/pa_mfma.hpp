@@ -1,4 +1,5 @@
-// libpa matrix-core bodies: shared prefixes of a group and several causal queries per sequence.
+// libpa matrix-core body (blocks shared by a group of sequences; several causal queries per
+// sequence) and the kernels built on it.
 #ifndef PA_PA_MFMA_HPP
 #define PA_PA_MFMA_HPP
 
@@ -10,10 +11,12 @@ namespace {
 // Where several queries meet the same K/V tile the work is a small dense
 // contraction: up to 16 queries against 16-token tiles.  Two uses:
 //   GROUP  a group of sequences that map common physical blocks (Sec. 4.4):
-//          one workgroup per (group, head) walks the group's tile list - every
-//          distinct block once, with the set of members that map it - and
-//          produces the finished output row of every member;
-//   MULTI  the last q_len tokens of one sequence as causal queries.
+//          the workgroup of a (group, head) walks the group's tile list - the
+//          blocks members share, once each, with the set of members that map
+//          it - and leaves every member's unnormalised partial result in LDS
+//          (group_item adds the members' own blocks and finishes the rows);
+//   MULTI  the last q_len tokens of one sequence as causal queries; the
+//          finished rows are written.
 // Wave w takes tiles w, w+W, ...  Per 16-token tile:
 //   S^T = K Q^T   8 x v_mfma_f32_16x16x16 (f16 or bf16 operands, fp32 result):
 //                 A rows are tokens, B columns are queries.  The K tile is
