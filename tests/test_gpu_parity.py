@@ -370,6 +370,31 @@ def test_deterministic_and_placement_invariant(pa):
         assert np.array_equal(to_np(out, w.dtype).view(np.uint8), a.view(np.uint8)), "placement changed the bits"
 
 
+def test_shared_decode_deterministic_and_placement_invariant(pa):
+    # the sharing-aware path: grouping looks at which table entries are equal, never at their values
+    for w in (W.config5(seed=71, num_seqs=14, H=3, min_len=100, max_len=600),
+              W.config3(seed=72, num_groups=5, H=3, prompt_median=50, prompt_cap=200, max_out=60)):
+        v = W.make_values(w)
+        dw = DeviceWorkload(w, v)
+        gpu_cache_ops(pa, dw)
+        a = to_np(gpu_decode_shared(pa, dw), w.dtype)
+        b = to_np(gpu_decode_shared(pa, dw), w.dtype)
+        assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), "run-to-run difference"
+        perm = np.random.default_rng(5).permutation(w.num_blocks)
+        inv = np.argsort(perm)
+        B = w.block_size
+        bt = w.block_tables.copy()
+        for s in range(w.num_seqs):
+            nb = (int(w.context_lens[s]) + B - 1) // B
+            bt[s, :nb] = perm[bt[s, :nb]]
+        moved = DeviceWorkload(w, v)
+        moved.k_cache = dw.k_cache[to_dev(inv)].contiguous()
+        moved.v_cache = dw.v_cache[to_dev(inv)].contiguous()
+        moved.block_tables = to_dev(bt)
+        c = to_np(gpu_decode_shared(pa, moved), w.dtype)
+        assert np.array_equal(c.view(np.uint8), a.view(np.uint8)), "placement changed the bits"
+
+
 def test_reshape_and_cache_prefill_sized(pa):
     # thousands of tokens in one call (a prompt phase storing its KV), with skipped padding tokens
     rng = np.random.default_rng(21)
