@@ -186,3 +186,66 @@ def test_bf16_rounding_helper():
     assert back[0] == 1.0 and back[1] == 1.0 and back[2] == np.float32(1.015625)
     assert back[3] == -2.5
     assert np.all(np.abs(back[:5] - x[:5]) <= np.abs(x[:5]) * 2.0 ** -8)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_block_manager_random_walk_keeps_its_books(seed):
+    """A seeded random mix of allocate / fork / append / free (Sec. 5.2: every decoding algorithm
+    reduces to these) against a shadow model that stores every sequence's tokens explicitly.
+    After every operation: reference counts equal the number of tables that map each block, free
+    plus mapped blocks are the whole pool, and replaying the queued copies and the writes on a
+    shadow pool gives every sequence exactly its own tokens back (copy-on-write never lets one
+    sequence see another's writes)."""
+    from collections import Counter
+    from harness.blocks import BlockManager
+    rng = np.random.default_rng(100 + seed)
+    B = int(rng.choice([2, 4, 16]))
+    NB = 96
+    mgr = BlockManager(NB, B, order=rng.permutation(NB))
+    pool = np.full((NB, B), -1, dtype=np.int64)          # shadow K/V: one integer per slot
+    live, truth = [], []                                  # sequences and the token ids each should hold
+    next_token = [0]
+
+    def write(seq, toks, slot):
+        pool.reshape(-1)[slot] = next_token[0]
+        toks.append(next_token[0])
+        next_token[0] += 1
+
+    def flush_copies():
+        for src, dst in mgr.take_copies():
+            pool[dst] = pool[src]
+
+    for step in range(400):
+        op = rng.choice(["allocate", "fork", "append", "append", "append", "free"])
+        try:
+            if op == "allocate" or not live:
+                n = int(rng.integers(1, 3 * B))
+                if mgr.alloc.num_free * B < n:
+                    continue
+                s = mgr.allocate(n)
+                toks = []
+                for t in range(n):
+                    write(s, toks, mgr.slot_of(s, t))
+                live.append(s); truth.append(toks)
+            elif op == "fork":
+                i = int(rng.integers(0, len(live)))
+                live.append(mgr.fork(live[i])); truth.append(list(truth[i]))
+            elif op == "append":
+                i = int(rng.integers(0, len(live)))
+                if mgr.alloc.num_free == 0:
+                    continue
+                slot = mgr.append(live[i])
+                flush_copies()                            # the copy is executed before the write (Sec. 4.4)
+                write(live[i], truth[i], slot)
+            else:
+                i = int(rng.integers(0, len(live)))
+                mgr.free(live.pop(i)); truth.pop(i)
+        finally:
+            flush_copies()
+        mapped = Counter(pb for s in live for pb in s.blocks)
+        assert all(mgr.alloc.ref[pb] == mapped.get(pb, 0) for pb in range(NB))
+        assert mgr.alloc.num_free + len(mapped) == NB
+        for s, toks in zip(live, truth):
+            assert s.length == len(toks) and len(s.blocks) == (s.length + B - 1) // B
+            got = [int(pool.reshape(-1)[mgr.slot_of(s, t)]) for t in range(s.length)]
+            assert got == toks
