@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--partition", type=int, default=None,
                     help="partition_size for pa_decode (0 = one pass, -1 = library's choice); "
                          "default: the library's choice")
+    ap.add_argument("--cache-allocation", default="one", choices=["one", "two"],
+                    help="one: K and V of the layer carved from one device allocation; two: an allocation each")
     ap.add_argument("--launch", default="eager", choices=["eager", "graph"],
                     help="eager: three library calls per step (default; measured 179 us per step); "
                          "graph: the step is captured once in a HIP graph and replayed (186 us: the replay "
@@ -402,16 +404,20 @@ def main():
         return t.to(dev)
 
     # K and V of the layer are carved from one device allocation (K first, V at the next
-    # 2 MiB boundary), as a serving engine lays out a layer's cache.  At this shape the decode
-    # kernel runs ~2% faster than with two separate allocations (measured: 171.5 against 175.5 us).
+    # 2 MiB boundary), as a serving engine lays out a layer's cache; --cache-allocation two
+    # gives each its own (measured within 0.3% of each other at the OPT-13B shape).
     hk, hv = torch.from_numpy(np.ascontiguousarray(kc)), torch.from_numpy(np.ascontiguousarray(vc))
     if w.dtype == "bf16":
         hk, hv = hk.view(torch.bfloat16), hv.view(torch.bfloat16)
     nbytes = hk.numel() * hk.element_size()
     v_off = (nbytes + (1 << 21) - 1) >> 21 << 21
-    arena = torch.empty(v_off + nbytes, dtype=torch.uint8, device=dev)
-    d_kc = arena[:nbytes].view(hk.dtype).view(hk.shape)
-    d_vc = arena[v_off:v_off + nbytes].view(hk.dtype).view(hk.shape)
+    if args.cache_allocation == "one":
+        arena = torch.empty(v_off + nbytes, dtype=torch.uint8, device=dev)
+        d_kc = arena[:nbytes].view(hk.dtype).view(hk.shape)
+        d_vc = arena[v_off:v_off + nbytes].view(hk.dtype).view(hk.shape)
+    else:
+        d_kc = torch.empty(hk.shape, dtype=hk.dtype, device=dev)
+        d_vc = torch.empty(hk.shape, dtype=hk.dtype, device=dev)
     d_kc.copy_(hk)
     d_vc.copy_(hv)
     del hk, hv
@@ -519,7 +525,7 @@ def main():
         "dtype": w.dtype, "accumulate": "f32", "data": "synthetic",
         "config": {"workload": w.name, "num_seqs": S, "num_heads": H, "head_dim": D, "block_size": B,
                    "num_blocks": w.num_blocks, "context_tokens": int(w.context_lens.sum()),
-                   "max_context_len": mcl, "partition_size": ps, "seed": w.seed, "decode": args.decode, "launch": args.launch, "cache_allocation": "K and V of the layer in one device allocation",
+                   "max_context_len": mcl, "partition_size": ps, "seed": w.seed, "decode": args.decode, "launch": args.launch, "cache_allocation": ("K and V of the layer in one device allocation" if args.cache_allocation == "one" else "K and V in separate device allocations"),
                    "kv_bytes_logical": kv_bytes, "kv_bytes_unique": kv_unique,
                    "step": "copy_blocks(0 pairs)+reshape_and_cache(T=S)+pa_decode"},
         "query_tokens_per_s": S / (ms_per_step * 1e-3),

@@ -70,7 +70,8 @@ enum SharedSteps { SHARED_PLAN = 1, SHARED_DECODE = 2 };
 template <int DT, int D, int B, int W, int MODE>
 void launch_decode_kernel(const DecodeArgs &a, unsigned items)
 {
-    hipLaunchKernelGGL((pa_decode_kernel<DT, D, B, W, kChunksPerTrip, MODE>), dim3(items * (unsigned)a.p.H),
+    hipLaunchKernelGGL((pa_decode_kernel<DT, D, B, W, MODE == MODE_PART ? kPartChunksPerTrip : kChunksPerTrip, MODE>),
+                       dim3(items * (unsigned)a.p.H),
                        dim3(W * kWave), 0, a.stream, a.p);
 }
 

@@ -14,8 +14,8 @@ namespace {
 // load covers TPL = 64/LPT consecutive tokens; lane = g*LPT + c holds
 // dimensions [c*EPL, (c+1)*EPL) of token (base + g).  Work advances in chunks
 // of LPC loads (CT = LPC*TPL tokens, at most one block); wave w takes chunks
-// w, w+W, ...; U chunks (2*U*LPC KiB of K and V) are requested together
-// before any of them is used.
+// w, w+W, ...; the loads of U chunks (2*U*LPC KiB of K and V) are written
+// together ahead of their use, and the compiler spreads them over the trip.
 //
 // Each group g of lanes runs its own online softmax over the tokens it sees
 // (running maximum m, sum l, weighted V sum acc, all fp32, exponents in base
@@ -165,9 +165,9 @@ __device__ __forceinline__ void stream_range(const DecodeParams &P, const int s,
     const std::false_type full{};
     const std::true_type masked{};
 
-    // Steady state: U chunks per trip, all loads issued up front, then consumed
-    // in order, in one straight-line block (nothing loaded is carried across the
-    // back edge, so the compiler waits exactly for the fragment it needs next).
+    // Steady state: U chunks per trip in one straight-line block; nothing loaded is
+    // carried across the back edge, so the compiler is free to place each load where
+    // register pressure allows and waits exactly for the fragment it needs next.
     // Chunks before the last one of the range are full; the remainder loop takes
     // one chunk at a time with masking.  Latency is hidden by the other waves
     // resident on the SIMD.

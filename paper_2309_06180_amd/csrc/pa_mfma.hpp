@@ -361,7 +361,7 @@ __device__ __forceinline__ void group_item(const DecodeParams &P, const int bloc
             sq = s0 + j;
             n = P.context_lens[sq];
             const int own = P.ginfo[ginfo_own_start(P.S, sq)];
-            if (own < n) stream_range<DT, D, B, kChunksPerTripDevice>(P, sq, h, own, n, k, per, m, l, acc);
+            if (own < n) stream_range<DT, D, B, kGroupChunksPerTrip>(P, sq, h, own, n, k, per, m, l, acc);
         }
         if (g == 0) {
 #pragma unroll
@@ -408,7 +408,7 @@ __global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))
     } else {
         const int idx = (int)blockIdx.x - P.group_blocks;
         if (P.ginfo[ginfo_in_group(P.S, idx / P.H)]) return;
-        decode_body<DT, 128, B, W, kChunksPerTripDevice, MODE_SINGLE>(P, idx);
+        decode_body<DT, 128, B, W, kChunksPerTrip, MODE_SINGLE>(P, idx);
     }
 }
 
