@@ -32,15 +32,19 @@ namespace {
 //                 query does not see, are set to -inf by select; the running
 //                 maximum is kept per query (two cross-lane maxima per tile),
 //                 exp2 in fp32, the output rescaled only when a maximum moved.
-//   O += P V      32 x v_mfma_f32_16x16x4_f32: A = P in fp32 straight from the
-//                 softmax registers, B = the V fragments of the ordinary
-//                 coalesced load widened to fp32 (lane l: token l/16 + 4v,
-//                 dims 8*(l%16)+e; output column l%16 of MFMA e is dim
-//                 8*(l%16)+e).  fp32 operands keep P exact; the fp32 matrix
-//                 rate is still about three times what the HBM stream needs.
+//   O += P V      v_mfma_f32_16x16x16 again, 16 (f16) or 24 (bf16) per tile: A = P
+//                 straight from the softmax registers, cut into two or three
+//                 16-bit pieces that add up to P to fp32 accuracy (split_weights),
+//                 B = V: lane l needs dim 16e + l%16 of its four tokens, so the V
+//                 tile of the ordinary coalesced load is parked in the wave's LDS
+//                 region (where K was) and read back two bytes at a time.  (fp32
+//                 operands - v_mfma_f32_16x16x4_f32 with V widened in registers,
+//                 no LDS round trip - cost 1024 instead of 256-384 matrix-pipe
+//                 cycles per tile and were 2-7% slower end to end.)
 // K rows are read back in the order token(i) = i/4 + 4*(i%4) so that result
-// register v of lane l belongs to token l/16 + 4v, the token of V fragment v
-// in that lane: P never moves between lanes and V needs no transpose.
+// register v of lane l belongs to token l/16 + 4v: the four weights a lane holds
+// are exactly the A operand of the P V product (contraction slot 4*(l/16) + v
+// stands for token l/16 + 4v on both sides), so P never moves between lanes.
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
@@ -57,19 +61,44 @@ __device__ __forceinline__ float4_t mfma_qk(uint32_t a0, uint32_t a1, uint32_t b
                                                          __builtin_bit_cast(short4_t, b), c, 0, 0, 0);
 }
 
+// Softmax weights as 16-bit MFMA operands without giving up fp32 accuracy: P is cut
+// into pieces whose sum is P to about 2^-22 (f16: two pieces of 11 bits) or 2^-24
+// (bf16: three pieces of 8 bits); every piece times a 16-bit V element is exact in the
+// fp32 accumulator.  f16 has a narrow exponent range, so its weights carry a factor
+// 2^14 (the largest, 1.0, becomes 16384; anything that still underflows is below
+// 4e-9 of the largest weight); the factor is taken out when a wave's result is stored.
+template <int DT> struct WeightPieces { static constexpr int N = DT == PA_F16 ? 2 : 3; };
 template <int DT>
-__device__ __forceinline__ void widen8(float (&f)[8], const uint4 &v)
+__device__ __forceinline__ void split_weights(const float (&p)[4], uint32_t (&out)[WeightPieces<DT>::N][2])
 {
-    const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+    if (DT == PA_F16) {
+        typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+        float rest[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        if (DT == PA_F16) {
-            const half2_t h = __builtin_bit_cast(half2_t, u[i]);
-            f[2 * i] = (float)h.x;
-            f[2 * i + 1] = (float)h.y;
-        } else {
-            f[2 * i] = as_f32(u[i] << 16);
-            f[2 * i + 1] = as_f32(u[i] & 0xffff0000u);
+        for (int hh = 0; hh < 2; ++hh) {
+            const float a = p[2 * hh] * 16384.0f, b = p[2 * hh + 1] * 16384.0f;
+            const half2v hi = __builtin_bit_cast(half2v, __builtin_amdgcn_cvt_pkrtz(a, b));
+            out[0][hh] = __builtin_bit_cast(uint32_t, hi);
+            rest[2 * hh] = a - (float)hi.x;
+            rest[2 * hh + 1] = b - (float)hi.y;
+        }
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+            out[1][hh] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(rest[2 * hh], rest[2 * hh + 1]));
+    } else {
+        float rest[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) rest[v] = p[v];
+#pragma unroll
+        for (int pc = 0; pc < 3; ++pc) {
+            uint32_t top[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                top[v] = __builtin_bit_cast(uint32_t, rest[v]) & 0xffff0000u;   // the leading 8 bits of what is left
+                rest[v] -= as_f32(top[v]);
+            }
+            out[pc][0] = (top[0] >> 16) | top[1];
+            out[pc][1] = (top[2] >> 16) | top[3];
         }
     }
 }
@@ -85,6 +114,8 @@ __device__ __forceinline__ void mfma_body(const DecodeParams &P, const int block
     constexpr int64_t TILE_BYTES = (int64_t)B * ROW_BYTES;
     static_assert(DT != PA_F32 && B % 16 == 0, "two-byte elements, whole 16-token tiles per block");
     static_assert(GQ <= 16, "one MFMA row per query");
+    constexpr int PIECES = WeightPieces<DT>::N;
+    constexpr float kUnscale = DT == PA_F16 ? 1.0f / 16384.0f : 1.0f;
 
     const int lane = threadIdx.x & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -149,11 +180,14 @@ __device__ __forceinline__ void mfma_body(const DecodeParams &P, const int block
     // Rows are padded by 16 bytes so that the 16 rows one read touches fall in different
     // banks.  When the wave is done the region holds its partial result for the merge.
     constexpr int K_ROW_PAD = ROW_BYTES + 16;
-    constexpr int REGION = (16 * K_ROW_PAD > GQ * D * 4) ? 16 * K_ROW_PAD : GQ * D * 4;
+    constexpr int V_ROW_PAD = ROW_BYTES + 32;
+    constexpr int REGION = (16 * V_ROW_PAD > GQ * D * 4) ? 16 * V_ROW_PAD : GQ * D * 4;
     __shared__ __align__(16) char sm_region[W][REGION];
     char *const kst = sm_region[w];
     const uint32_t kst_write = (uint32_t)(r * K_ROW_PAD + 16 * c);                      // + 4j rows
     const uint32_t kst_read = (uint32_t)((c / 4 + 4 * (c % 4)) * K_ROW_PAD + 16 * r);   // + 64cc bytes
+    const uint32_t vst_write = (uint32_t)(r * V_ROW_PAD + 16 * c);                      // + 4v rows
+    const uint32_t vst_read = (uint32_t)(r * V_ROW_PAD + 2 * c);                        // + 4v rows, + 32e bytes
 
     // one 16-token tile: first token t0 (position in the sequence), at byte `base` of
     // the caches; rows at or past `rows` hold no token any query here sees;
@@ -212,19 +246,36 @@ __device__ __forceinline__ void mfma_body(const DecodeParams &P, const int block
             }
             m = m_new;
         }
+        // the V tile takes the K tile's place in the wave's LDS region (K is in registers by now)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) *reinterpret_cast<uint4 *>(kst + vst_write + 4 * v * V_ROW_PAD) = vf[v];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         float p[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             p[v] = __builtin_amdgcn_exp2f(x[v] - m);
             lsum += p[v];
         }
+        // P as the A operand, split into 16-bit pieces whose sum is P to fp32 accuracy
+        uint32_t pa[PIECES][2];
+        split_weights<DT>(p, pa);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            float vv[8];
-            widen8<DT>(vv, vf[v]);
+        for (int e = 0; e < 8; ++e) {
+            // B operand of dims 16e .. 16e+15: lane l takes dim 16e + l%16 of its four tokens
+            uint32_t vb[2];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) O[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[v], vv[e], O[e], 0, 0, 0);
+            for (int hh = 0; hh < 2; ++hh) {
+                const uint32_t lo = *reinterpret_cast<const uint16_t *>(kst + vst_read + 4 * (2 * hh) * V_ROW_PAD + 32 * e);
+                const uint32_t hi = *reinterpret_cast<const uint16_t *>(kst + vst_read + 4 * (2 * hh + 1) * V_ROW_PAD + 32 * e);
+                vb[hh] = lo | (hi << 16);
+            }
+#pragma unroll
+            for (int pc = 0; pc < PIECES; ++pc) O[e] = mfma_qk<DT>(pa[pc][0], pa[pc][1], vb[0], vb[1], O[e]);
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     };
 
     if (MULTI) {
@@ -264,7 +315,7 @@ __device__ __forceinline__ void mfma_body(const DecodeParams &P, const int block
         const int qi = 4 * r + v;
         if (qi < members) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sm_acc(w)[qi][8 * c + e] = O[e][v];
+            for (int e = 0; e < 8; ++e) sm_acc(w)[qi][16 * e + c] = O[e][v] * kUnscale;
         }
     }
     if (r == 0 && c < members) {
