@@ -53,7 +53,8 @@ typedef enum {
     PA_ERR_ALIGN = 4,       /* a data pointer is not 16-byte aligned              */
     PA_ERR_WORKSPACE = 5,   /* workspace missing or too small                     */
     PA_ERR_HIP = 6,         /* the HIP runtime refused a launch or a copy         */
-    PA_ERR_INVALID = 7      /* pa_debug_validate found a bad index                */
+    PA_ERR_INVALID = 7,     /* pa_debug_validate found a bad index                */
+    PA_ERR_LIMIT = 8        /* pa_decode_static: the shape needs more than PA_STATIC_SCRATCH_BYTES */
 } pa_status;
 
 typedef enum { PA_F32 = 0, PA_F16 = 1, PA_BF16 = 2 } pa_dtype;
@@ -106,6 +107,29 @@ pa_status pa_decode(void *out, const void *q, const void *k_cache, const void *v
 size_t pa_decode_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t head_dim,
                                  int32_t block_size, int32_t max_context_len,
                                  int32_t partition_size);
+
+/*
+ * pa_decode_static - pa_decode for callers that cannot allocate or pass device
+ * scratch memory: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation.  Same arguments and result as pa_decode without the
+ * workspace: the split-context partials (max logit, exp-sum, partial sums) go
+ * to an array of PA_STATIC_SCRATCH_BYTES bytes that is part of the library's
+ * device image; each GPU the library runs on holds one until the process
+ * ends.  The call allocates and frees nothing.  A (shape, partition_size) for
+ * which pa_decode_workspace_bytes(...) exceeds PA_STATIC_SCRATCH_BYTES is
+ * refused with PA_ERR_LIMIT and nothing is launched.  partition_size = 0 uses
+ * no scratch at all.  All calls on one GPU share that GPU's array: calls that
+ * may overlap on one GPU (different streams, different threads) race on it
+ * and must be ordered by the caller.  Nothing in the array has to start at
+ * zero and nothing is kept between calls.
+ */
+#define PA_STATIC_SCRATCH_BYTES (16u << 20)
+pa_status pa_decode_static(void *out, const void *q, const void *k_cache, const void *v_cache,
+                           const int32_t *block_tables, int32_t max_blocks_per_seq,
+                           const int32_t *context_lens, int32_t num_seqs, int32_t num_heads,
+                           int32_t head_dim, int32_t block_size, int64_t num_blocks, pa_dtype dtype,
+                           float scale, int32_t max_context_len, int32_t partition_size,
+                           void *stream);
 
 /*
  * pa_decode_shared - pa_decode for batches whose sequences share physical

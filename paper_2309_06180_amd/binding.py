@@ -18,7 +18,7 @@ from .build import LIB
 PA_F32, PA_F16, PA_BF16 = 0, 1, 2
 PA_PARTITION_AUTO = -1
 
-EXPORTS = ("pa_decode", "pa_decode_workspace_bytes", "pa_decode_shared", "pa_decode_shared_workspace_bytes", "pa_shared_plan", "pa_decode_shared_planned", "pa_decode_multi", "pa_reshape_and_cache", "pa_copy_blocks", "pa_swap_blocks",
+EXPORTS = ("pa_decode", "pa_decode_workspace_bytes", "pa_decode_static", "pa_decode_shared", "pa_decode_shared_workspace_bytes", "pa_shared_plan", "pa_decode_shared_planned", "pa_decode_multi", "pa_reshape_and_cache", "pa_copy_blocks", "pa_swap_blocks",
            "pa_debug_validate", "pa_stream_read", "pa_status_string", "pa_version")
 
 _DT = {torch.float32: PA_F32, torch.float16: PA_F16, torch.bfloat16: PA_BF16}
@@ -45,6 +45,9 @@ def load_library() -> ctypes.CDLL:
     lib.pa_decode.restype = ctypes.c_int
     lib.pa_decode.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i64, ctypes.c_int,
                               ctypes.c_float, i32, i32, vp, sz, vp]
+    lib.pa_decode_static.restype = ctypes.c_int
+    lib.pa_decode_static.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i64, ctypes.c_int,
+                                     ctypes.c_float, i32, i32, vp]
     lib.pa_decode_workspace_bytes.restype = sz
     lib.pa_decode_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
     lib.pa_decode_shared.restype = ctypes.c_int
@@ -126,6 +129,26 @@ def pa_decode(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache
         _dev(v_cache, "v_cache", q.dtype), _dev(block_tables, "block_tables", torch.int32),
         block_tables.shape[1], _dev(context_lens, "context_lens", torch.int32), S, H, D, B, NB, dt,
         float(scale), int(max_context_len), int(partition_size), ws_ptr, ws_bytes, _stream()))
+
+
+PA_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def pa_decode_static(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                     block_tables: torch.Tensor, context_lens: torch.Tensor, block_size: int, scale: float,
+                     max_context_len: int, partition_size: int = 0) -> None:
+    """pa_decode whose split-context partials live in the library's own static device array."""
+    S, H, D = q.shape
+    NB, H2, B, D2 = k_cache.shape
+    if (H2, B, D2) != (H, block_size, D) or v_cache.shape != k_cache.shape or out.shape != q.shape:
+        raise ValueError("inconsistent shapes")
+    if block_tables.dim() != 2 or block_tables.shape[0] != S or context_lens.shape != (S,):
+        raise ValueError("block_tables must be [S][MB], context_lens [S]")
+    _check(load_library().pa_decode_static(
+        _dev(out, "out", q.dtype), _dev(q, "q"), _dev(k_cache, "k_cache", q.dtype),
+        _dev(v_cache, "v_cache", q.dtype), _dev(block_tables, "block_tables", torch.int32),
+        block_tables.shape[1], _dev(context_lens, "context_lens", torch.int32), S, H, D, B, NB, _DT[q.dtype],
+        float(scale), int(max_context_len), int(partition_size), _stream()))
 
 
 def pa_decode_shared_workspace_bytes(num_seqs: int, num_heads: int, head_dim: int,

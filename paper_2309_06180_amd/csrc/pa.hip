@@ -30,6 +30,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "pa.h"
@@ -40,7 +41,37 @@
 #include "pa_groups.hpp"
 #include "pa_cache_ops.hpp"
 
+// ---- static scratch of pa_decode_static ------------------------------------------
+// Split-context partials for callers that cannot hand over a workspace.  Every device the
+// library runs on holds its own copy of the array until the process ends.  In host code the
+// array's name is only a handle: the device address is asked for once per device, with that
+// device current, and kept; kernels and copies are given that address, never the name.
+static __device__ __align__(256) unsigned char scratch[PA_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+pa_status static_scratch(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return PA_ERR_HIP;
+    }
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        // two threads racing here ask twice and get the same answer
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return PA_ERR_HIP;
+        }
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *ptr = p;
+    return PA_OK;
+}
 
 // ---- host side -----------------------------------------------------------------
 int elem_bytes(pa_dtype dt) { return dt == PA_F32 ? 4 : 2; }
@@ -279,6 +310,7 @@ const char *pa_status_string(pa_status st)
     case PA_ERR_WORKSPACE: return "workspace missing or too small";
     case PA_ERR_HIP: return "HIP runtime error";
     case PA_ERR_INVALID: return "invalid index found by pa_debug_validate";
+    case PA_ERR_LIMIT: return "needs more scratch than the library's static array holds";
     }
     return "unknown status";
 }
@@ -293,12 +325,14 @@ size_t pa_decode_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t he
     return (size_t)num_seqs * num_heads * parts * ((size_t)head_dim + 2) * sizeof(float);
 }
 
-pa_status pa_decode(void *out, const void *q, const void *k_cache, const void *v_cache,
-                    const int32_t *block_tables, int32_t max_blocks_per_seq,
-                    const int32_t *context_lens, int32_t num_seqs, int32_t num_heads,
-                    int32_t head_dim, int32_t block_size, int64_t num_blocks, pa_dtype dtype,
-                    float scale, int32_t max_context_len, int32_t partition_size, void *workspace,
-                    size_t workspace_bytes, void *stream)
+// pa_decode proper.  `static_limit` > 0 marks the caller as pa_decode_static: the workspace is
+// the library's own static array of that many bytes and a larger need is refused as such.
+static pa_status decode_core(void *out, const void *q, const void *k_cache, const void *v_cache,
+                             const int32_t *block_tables, int32_t max_blocks_per_seq,
+                             const int32_t *context_lens, int32_t num_seqs, int32_t num_heads,
+                             int32_t head_dim, int32_t block_size, int64_t num_blocks, pa_dtype dtype,
+                             float scale, int32_t max_context_len, int32_t partition_size, void *workspace,
+                             size_t workspace_bytes, size_t static_limit, void *stream)
 {
     if (num_seqs < 0 || num_heads <= 0 || head_dim <= 0 || block_size <= 0 || num_blocks <= 0 ||
         max_blocks_per_seq <= 0 || max_context_len < 0)
@@ -328,6 +362,7 @@ pa_status pa_decode(void *out, const void *q, const void *k_cache, const void *v
         a.p.max_parts = (max_context_len + partition_size - 1) / partition_size;
         const size_t need = pa_decode_workspace_bytes(num_seqs, num_heads, head_dim, block_size,
                                                       max_context_len, partition_size);
+        if (static_limit && need > static_limit) return PA_ERR_LIMIT;
         if (!workspace || workspace_bytes < need) return PA_ERR_WORKSPACE;
         if (!aligned16(workspace)) return PA_ERR_ALIGN;
         if ((int64_t)num_seqs * num_heads * a.p.max_parts > 0x7fffffff) return PA_ERR_SHAPE;
@@ -337,6 +372,34 @@ pa_status pa_decode(void *out, const void *q, const void *k_cache, const void *v
     if (!dispatch_decode(a, dtype, head_dim, block_size, partition_size > 0 ? PLAN_PART : PLAN_SINGLE))
         return PA_ERR_UNSUPPORTED;
     return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
+}
+
+pa_status pa_decode(void *out, const void *q, const void *k_cache, const void *v_cache,
+                    const int32_t *block_tables, int32_t max_blocks_per_seq,
+                    const int32_t *context_lens, int32_t num_seqs, int32_t num_heads,
+                    int32_t head_dim, int32_t block_size, int64_t num_blocks, pa_dtype dtype,
+                    float scale, int32_t max_context_len, int32_t partition_size, void *workspace,
+                    size_t workspace_bytes, void *stream)
+{
+    return decode_core(out, q, k_cache, v_cache, block_tables, max_blocks_per_seq, context_lens, num_seqs,
+                       num_heads, head_dim, block_size, num_blocks, dtype, scale, max_context_len,
+                       partition_size, workspace, workspace_bytes, 0, stream);
+}
+
+pa_status pa_decode_static(void *out, const void *q, const void *k_cache, const void *v_cache,
+                           const int32_t *block_tables, int32_t max_blocks_per_seq,
+                           const int32_t *context_lens, int32_t num_seqs, int32_t num_heads,
+                           int32_t head_dim, int32_t block_size, int64_t num_blocks, pa_dtype dtype,
+                           float scale, int32_t max_context_len, int32_t partition_size, void *stream)
+{
+    void *ws = nullptr;
+    if (num_seqs > 0) {
+        const pa_status st = static_scratch(&ws);
+        if (st != PA_OK) return st;
+    }
+    return decode_core(out, q, k_cache, v_cache, block_tables, max_blocks_per_seq, context_lens, num_seqs,
+                       num_heads, head_dim, block_size, num_blocks, dtype, scale, max_context_len,
+                       partition_size, ws, PA_STATIC_SCRATCH_BYTES, PA_STATIC_SCRATCH_BYTES, stream);
 }
 
 size_t pa_decode_shared_workspace_bytes(int32_t num_seqs, int32_t num_heads, int32_t head_dim,

@@ -33,8 +33,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_version_and_status_strings(lib):
     assert lib.pa_version() >= 1
-    seen = {lib.pa_status_string(c) for c in range(8)}
-    assert len(seen) == 8 and all(s for s in seen)
+    seen = {lib.pa_status_string(c) for c in range(9)}
+    assert len(seen) == 9 and all(s for s in seen)
 
 
 def test_workspace_size_formula(lib):
