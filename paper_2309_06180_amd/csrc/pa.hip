@@ -244,28 +244,31 @@ int auto_partition(int S, int H, int max_context_len)
     return ps >= max_context_len ? 0 : (int)ps;
 }
 
-// Waves per (sequence, 16 queries, head) item.  Each wave holds 16 query rows of partial results
-// (8 KiB of LDS).  With few queries per sequence the grid is small and the items are pure
-// streaming: eight waves read faster (195 against 202 us at the OPT-13B shape, q_len <= 4).
-// With many query blocks per sequence the items re-read K/V out of L2 and are bound by the
-// matrix pipe; four waves, four items per compute unit, do better there (2.07 against 2.51 ms
-// at q_len 256).
-template <int DT, int W>
-bool launch_multi_w(const DecodeArgs &a, int B, unsigned blocks)
+// Several queries per sequence.  Up to 16 of them: one workgroup of eight waves per (sequence,
+// head) that split the tiles.  More: one workgroup of four waves per (sequence, 64 queries,
+// head) that share every tile through LDS.
+template <int DT, int B>
+void launch_multi_b(const DecodeArgs &a, int max_q_len)
 {
-    switch (B) {
-    case 16: hipLaunchKernelGGL((pa_decode_multi_kernel<DT, 16, W>), dim3(blocks), dim3(W * kWave), 0, a.stream, a.p); return true;
-    case 32: hipLaunchKernelGGL((pa_decode_multi_kernel<DT, 32, W>), dim3(blocks), dim3(W * kWave), 0, a.stream, a.p); return true;
-    case 64: hipLaunchKernelGGL((pa_decode_multi_kernel<DT, 64, W>), dim3(blocks), dim3(W * kWave), 0, a.stream, a.p); return true;
-    case 128: hipLaunchKernelGGL((pa_decode_multi_kernel<DT, 128, W>), dim3(blocks), dim3(W * kWave), 0, a.stream, a.p); return true;
+    if (max_q_len <= 16) {
+        hipLaunchKernelGGL((pa_multi_split_kernel<DT, B, 8>), dim3((unsigned)a.p.S * (unsigned)a.p.H), dim3(8 * kWave), 0,
+                           a.stream, a.p);
+    } else {
+        const unsigned blocks = (unsigned)a.p.S * (unsigned)a.p.q_blocks * (unsigned)a.p.H;
+        hipLaunchKernelGGL((pa_multi_block_kernel<DT, B>), dim3(blocks), dim3(4 * kWave), 0, a.stream, a.p);
     }
-    return false;
 }
 
 template <int DT>
-bool launch_multi(const DecodeArgs &a, int B, unsigned blocks, int max_q_len)
+bool launch_multi(const DecodeArgs &a, int B, int max_q_len)
 {
-    return max_q_len <= 8 ? launch_multi_w<DT, 8>(a, B, blocks) : launch_multi_w<DT, 4>(a, B, blocks);
+    switch (B) {
+    case 16: launch_multi_b<DT, 16>(a, max_q_len); return true;
+    case 32: launch_multi_b<DT, 32>(a, max_q_len); return true;
+    case 64: launch_multi_b<DT, 64>(a, max_q_len); return true;
+    case 128: launch_multi_b<DT, 128>(a, max_q_len); return true;
+    }
+    return false;
 }
 
 void fill_common(DecodeArgs &a, void *out, const void *q, const void *k_cache, const void *v_cache,
@@ -506,7 +509,7 @@ pa_status pa_decode_multi(void *out, const void *q, const void *k_cache, const v
     if (num_seqs == 0 || max_q_len == 0) return PA_OK;
     if (!out || !q || !k_cache || !v_cache || !block_tables || !context_lens || !q_start) return PA_ERR_NULL;
     if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return PA_ERR_ALIGN;
-    const int64_t q_blocks = (max_q_len + 15) / 16;
+    const int64_t q_blocks = max_q_len <= 16 ? 1 : (max_q_len + 63) / 64;
     const int64_t blocks = (int64_t)num_seqs * q_blocks * num_heads;
     if (blocks > 0x7fffffff) return PA_ERR_SHAPE;
     DecodeArgs a;
@@ -515,8 +518,8 @@ pa_status pa_decode_multi(void *out, const void *q, const void *k_cache, const v
                 num_heads, scale, stream);
     a.p.q_start = q_start;
     a.p.q_blocks = (int32_t)q_blocks;
-    const bool ok = dtype == PA_F16 ? launch_multi<PA_F16>(a, block_size, (unsigned)blocks, max_q_len)
-                                    : launch_multi<PA_BF16>(a, block_size, (unsigned)blocks, max_q_len);
+    const bool ok = dtype == PA_F16 ? launch_multi<PA_F16>(a, block_size, max_q_len)
+                                    : launch_multi<PA_BF16>(a, block_size, max_q_len);
     if (!ok) return PA_ERR_UNSUPPORTED;
     return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
 }

@@ -356,16 +356,411 @@ __device__ __forceinline__ void mfma_body(const DecodeParams &P, const int block
     }
 }
 
-// Several query tokens per sequence (the tail of a prompt over an already cached
-// prefix, Sec. 4.4 "shared prefix"; or draft tokens to verify): grid =
-// (sequence, block of 16 queries, head).
-// (at least four waves per SIMD, i.e. at most 128 VGPRs: otherwise the compiler takes 136 and a
-// third of the residency is lost)
+// ---- the tile engine for gfx950 ---------------------------------------------
+// One step of attention for up to 16 queries against one 16-token K/V tile that sits in
+// LDS, with the matrix instructions of CDNA4 (k = 32) and its transposing LDS read.
+//
+// A wave owns 16 query columns: lane l = 16g + c holds query c.
+//   S^T = K Q^T   4 x v_mfma_f32_16x16x32: A = K (lane: token row c, 16 bytes of it per step,
+//                 ds_read_b128 out of the padded LDS tile), B = Q^T (lane: query c, the same
+//                 byte ranges of the query row, kept in registers).  Result: lane holds
+//                 tokens 4g .. 4g+3 of query c.
+//   softmax       per query, running maximum and sum kept in the lane (replicated over g);
+//                 two cross-lane maxima per tile, by v_permlane16_swap / v_permlane32_swap.
+//   O^T += V^T P^T  8 x v_mfma_f32_16x16x32: B = P^T (lane: query c), A = V^T (lane: head
+//                 dimension 16e + c, four tokens 4g .. 4g+3 fetched with one
+//                 ds_read_b64_tr_b16).  The result keeps query c in lane c, so rescaling
+//                 the output when a maximum moves needs no cross-lane traffic.
+// A 16-bit P would eat the tolerance, so P is cut into two 16-bit pieces whose sum is P to
+// 2^-18 (bf16, both pieces rounded to nearest) or 2^-21 (f16, with a factor 2^14 that keeps
+// small weights in range).  The contraction of the PV instruction is 32 deep and the tile
+// has 16 tokens: slots 8g + 0..3 carry the leading pieces and slots 8g + 4..7 the trailing
+// pieces of tokens 4g .. 4g+3 against the same V values, so one instruction applies both.
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2v_t __attribute__((ext_vector_type(2)));
+
+constexpr int kTileTokens = 16;
+constexpr int kKPitch = 256 + 16;   // 16 rows of one ds_read_b128 fall in 16 different bank groups
+constexpr int kVPitch = 256 + 32;   // 8 rows of one half-wave transposing read likewise
+constexpr int kTileLds = kTileTokens * (kKPitch + kVPitch);   // K tile, then V tile
+
+template <int DT>
+__device__ __forceinline__ float4_t mfma_k32(const uint4 &a, const uint4 &b, float4_t c)
+{
+    if (DT == PA_F16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a),
+                                                      __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+
+// maximum / sum over the four lanes that hold the same query (l, l^16, l^32, l^48)
+__device__ __forceinline__ float quad_rows_max(float x)
+{
+    auto a = __builtin_amdgcn_permlane16_swap(as_u32(x), as_u32(x), false, false);
+    x = fmaxf(as_f32(a[0]), as_f32(a[1]));
+    auto b = __builtin_amdgcn_permlane32_swap(as_u32(x), as_u32(x), false, false);
+    return fmaxf(as_f32(b[0]), as_f32(b[1]));
+}
+__device__ __forceinline__ float quad_rows_sum(float x)
+{
+    auto a = __builtin_amdgcn_permlane16_swap(as_u32(x), as_u32(x), false, false);
+    x = as_f32(a[0]) + as_f32(a[1]);
+    auto b = __builtin_amdgcn_permlane32_swap(as_u32(x), as_u32(x), false, false);
+    return as_f32(b[0]) + as_f32(b[1]);
+}
+
+// the four weights of a lane as the B operand: leading pieces in slots 0..3, trailing in 4..7
+template <int DT>
+__device__ __forceinline__ uint4 weight_operand(const float (&p)[4])
+{
+    uint4 o;
+    if (DT == PA_F16) {
+        typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+        const float a0 = p[0] * 16384.0f, a1 = p[1] * 16384.0f, a2 = p[2] * 16384.0f, a3 = p[3] * 16384.0f;
+        const half2v h01 = __builtin_bit_cast(half2v, __builtin_amdgcn_cvt_pkrtz(a0, a1));
+        const half2v h23 = __builtin_bit_cast(half2v, __builtin_amdgcn_cvt_pkrtz(a2, a3));
+        o.x = __builtin_bit_cast(uint32_t, h01);
+        o.y = __builtin_bit_cast(uint32_t, h23);
+        o.z = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a0 - (float)h01.x, a1 - (float)h01.y));
+        o.w = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a2 - (float)h23.x, a3 - (float)h23.y));
+    } else {
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            hi[v] = Traits<PA_BF16>::rne(p[v]);
+            lo[v] = Traits<PA_BF16>::rne(p[v] - as_f32(hi[v] << 16));
+        }
+        o.x = hi[0] | (hi[1] << 16);
+        o.y = hi[2] | (hi[3] << 16);
+        o.z = lo[0] | (lo[1] << 16);
+        o.w = lo[2] | (lo[3] << 16);
+    }
+    return o;
+}
+
+// query-side state of a wave
+struct QueryCols {
+    uint4 qf[4];       // Q^T operand: bytes [64cc + 16g, +16) of the row of query c
+    float4_t O[8];     // O^T: O[e][v] = output dimension 16e + 4g + v of query c (unnormalised)
+    float m, lsum;     // running maximum (log2 units); exp-sum over this lane's tokens
+    int limit;         // last token position query c sees; -1 if column c holds no query
+};
+
+template <int DT>
+__device__ __forceinline__ void query_cols_init(QueryCols &Q, const void *q, int64_t row, int H, int h, bool present,
+                                                int limit)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int g = lane / 16;
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) {
+        Q.qf[cc] = make_uint4(0, 0, 0, 0);
+        if (present)
+            Q.qf[cc] = *reinterpret_cast<const uint4 *>(static_cast<const char *>(q) + (row * H + h) * 256 + 64 * cc + 16 * g);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) Q.O[e] = float4_t{0.f, 0.f, 0.f, 0.f};
+    Q.m = kNegBig;
+    Q.lsum = 0.f;
+    Q.limit = present ? limit : -1;
+}
+
+// One tile: kt / vt point at the K and V tile in LDS (rows kKPitch / kVPitch apart), its first
+// token is position t0; `mask` = query columns that map the tile; `check` = some entry may
+// need masking (a column outside the mask, or a token past a query's limit).  V rows that
+// hold no token any query sees must have been zeroed by whoever filled the tile.
+template <int DT>
+__device__ __forceinline__ void tile_step(QueryCols &Q, const char *kt, const char *vt, int t0, uint32_t mask,
+                                          bool check, float scale_log2)
+{
+    typedef short4_t __attribute__((address_space(3))) *lds_tr_ptr;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int g = lane / 16, c = lane % 16;
+    uint4 kf[4];
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) kf[cc] = *reinterpret_cast<const uint4 *>(kt + c * kKPitch + 16 * g + 64 * cc);
+    float4_t S = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) S = mfma_k32<DT>(kf[cc], Q.qf[cc], S);
+    float x[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) x[v] = S[v] * scale_log2;
+    if (check) {
+        // by select, never by multiplying: rows past the stored tokens may hold anything
+        const bool mine = (mask >> c) & 1u;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) x[v] = (mine && t0 + 4 * g + v <= Q.limit) ? x[v] : -INFINITY;
+    }
+    const float tmax = quad_rows_max(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])));
+    const float m_new = fmaxf(Q.m, tmax);
+    if (__any(m_new > Q.m)) {
+        const float alpha = __builtin_amdgcn_exp2f(Q.m - m_new);
+        Q.lsum *= alpha;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Q.O[e][v] *= alpha;
+        }
+        Q.m = m_new;
+    }
+    float p[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        p[v] = __builtin_amdgcn_exp2f(x[v] - Q.m);
+        Q.lsum += p[v];
+    }
+    const uint4 pw = weight_operand<DT>(p);
+    // V^T operand of dimensions 16e .. 16e+15: in lane group g, lane 4t + u fetches 8 bytes of
+    // token row 4g + t at dimension 16e + 4u; the transposing read hands lane c dimension
+    // 16e + c of tokens 4g .. 4g+3
+    const char *vsrc = vt + (4 * g + c / 4) * kVPitch + 8 * (c % 4);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const short4_t va = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_tr_ptr)(vsrc + 32 * e));
+        const uint2 v2 = __builtin_bit_cast(uint2, va);
+        Q.O[e] = mfma_k32<DT>(make_uint4(v2.x, v2.y, v2.x, v2.y), pw, Q.O[e]);
+    }
+}
+
+// A tile on its way from HBM to LDS: the same coalesced 1 KiB-per-instruction loads as the
+// single-query kernel (lane 16r + c: 16 bytes at column 16c of token rows r, r+4, r+8, r+12).
+struct TileRegs {
+    uint4 k[4], v[4];
+};
+__device__ __forceinline__ void tile_fetch(TileRegs &R, const char *k_cache, const char *v_cache, int64_t base)
+{
+    const uint32_t off = (uint32_t)(threadIdx.x & (kWave - 1)) * 16u;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) R.k[j] = load16_stream(k_cache + base + off + 1024 * j);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) R.v[j] = load16_stream(v_cache + base + off + 1024 * j);
+}
+// rows at or past `rows` hold no token that any query of the tile sees: their V is zeroed
+__device__ __forceinline__ void tile_store(TileRegs &R, char *kt, char *vt, int rows, bool check)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int r = lane / 16, c = lane % 16;
+    if (check) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool unseen = r + 4 * j >= rows;
+            R.v[j].x = unseen ? 0u : R.v[j].x;
+            R.v[j].y = unseen ? 0u : R.v[j].y;
+            R.v[j].z = unseen ? 0u : R.v[j].z;
+            R.v[j].w = unseen ? 0u : R.v[j].w;
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) *reinterpret_cast<uint4 *>(kt + (r + 4 * j) * kKPitch + 16 * c) = R.k[j];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) *reinterpret_cast<uint4 *>(vt + (r + 4 * j) * kVPitch + 16 * c) = R.v[j];
+}
+
+// ---- several query tokens per sequence ----------------------------------------
+// (the tail of a prompt over an already cached prefix, Sec. 4.4 "shared prefix"; or draft
+// tokens to verify).  Query i of sequence s sits at position n - q_len + i and sees tokens
+// 0 .. n - q_len + i.
+//
+// Up to 16 queries per sequence: grid = (sequence, head); the W waves of the workgroup share
+// the 16 query columns and split the tiles (wave w takes tiles w, w+W, ...), each staging
+// its tiles in an LDS region of its own with the next tile's loads in flight meanwhile; the
+// waves' partial results are merged through LDS at the end.
 template <int DT, int B, int W>
-__global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) void pa_decode_multi_kernel(
+__global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) void pa_multi_split_kernel(
     const DecodeParams P)
 {
-    mfma_body<DT, B, W, 16, true>(P, (int)blockIdx.x, nullptr, nullptr, nullptr);
+    using Tr = Traits<DT>;
+    constexpr int D = 128, ROW_BYTES = 256;
+    constexpr int64_t TILE_BYTES = (int64_t)B * ROW_BYTES;
+    static_assert(DT != PA_F32 && B % kTileTokens == 0, "two-byte elements, whole 16-token tiles per block");
+    constexpr float kUnscale = DT == PA_F16 ? 1.0f / 16384.0f : 1.0f;
+    __shared__ __align__(16) char sm_region[W][kTileLds];
+    __shared__ float sm_m[W][16], sm_l[W][16];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int g = lane / 16, c = lane % 16;
+    const int H = P.H;
+    const int h = blockIdx.x % H;
+    const int s = blockIdx.x / H;
+    const int n = P.context_lens[s];
+    const int qs = P.q_start[s];
+    const int qlen = P.q_start[s + 1] - qs;
+    if (qlen <= 0 || n <= 0) return;
+    const int members = qlen < 16 ? qlen : 16;
+    const int t_lo = n - qlen + 1;             // tokens the first query sees
+    const int t_hi = n - qlen + members;       // tokens the last one of these 16 sees
+    const int ntiles = (t_hi + kTileTokens - 1) / kTileTokens;
+
+    QueryCols Q;
+    query_cols_init<DT>(Q, P.q, (int64_t)qs + c, H, h, c < members, t_lo - 1 + c);
+    const int32_t *__restrict__ table = P.block_tables + (int64_t)s * P.max_blocks;
+    char *const kt = sm_region[w];
+    char *const vt = kt + kTileTokens * kKPitch;
+
+    auto base_of = [&](int ti) -> int64_t {
+        const int t0 = ti * kTileTokens;
+        const int pb = table[t0 / B];            // wave-uniform: a scalar load
+        return ((int64_t)pb * H + h) * TILE_BYTES + (int64_t)(t0 % B) * ROW_BYTES;
+    };
+    TileRegs R;
+    if (w < ntiles) tile_fetch(R, P.k_cache, P.v_cache, base_of(w));
+    for (int ti = w; ti < ntiles; ti += W) {
+        const int t0 = ti * kTileTokens;
+        // masking starts where the tile reaches past what the first query sees
+        const bool check = t0 + kTileTokens > t_lo;
+        tile_store(R, kt, vt, t_hi - t0, check);
+        if (ti + W < ntiles) tile_fetch(R, P.k_cache, P.v_cache, base_of(ti + W));
+        __builtin_amdgcn_wave_barrier();
+        tile_step<DT>(Q, kt, vt, t0, 0xffffu, check, P.scale_log2);
+        __builtin_amdgcn_wave_barrier();
+    }
+    Q.lsum = quad_rows_sum(Q.lsum);
+
+    // merge the waves: each leaves its 16 x 128 partial sums in its own region
+    float(*const mine)[D] = reinterpret_cast<float(*)[D]>(sm_region[w]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        *reinterpret_cast<float4 *>(&mine[c][16 * e + 4 * g]) =
+            make_float4(Q.O[e][0] * kUnscale, Q.O[e][1] * kUnscale, Q.O[e][2] * kUnscale, Q.O[e][3] * kUnscale);
+    if (g == 0) {
+        sm_m[w][c] = Q.m;
+        sm_l[w][c] = Q.lsum;
+    }
+    __syncthreads();
+    constexpr int TPQ = W * kWave / 16;     // threads per query row
+    constexpr int DPT = D / TPQ;            // output dimensions per thread: 4 (eight waves) or 8 (four)
+    static_assert(DPT == 4 || DPT == 8, "workgroup width");
+    const int j = threadIdx.x / TPQ, d0 = (threadIdx.x % TPQ) * DPT;
+    if (j >= members) return;
+    float M = sm_m[0][j];
+#pragma unroll
+    for (int i = 1; i < W; ++i) M = fmaxf(M, sm_m[i][j]);
+    float l = 0.f, acc[DPT];
+#pragma unroll
+    for (int e = 0; e < DPT; ++e) acc[e] = 0.f;
+#pragma unroll
+    for (int i = 0; i < W; ++i) {
+        const float f = __builtin_amdgcn_exp2f(sm_m[i][j] - M);
+        l = __builtin_fmaf(sm_l[i][j], f, l);
+        const float *src = &reinterpret_cast<const float(*)[D]>(sm_region[i])[j][d0];
+#pragma unroll
+        for (int e = 0; e < DPT; ++e) acc[e] = __builtin_fmaf(src[e], f, acc[e]);
+    }
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+#pragma unroll
+    for (int e = 0; e < DPT; ++e) acc[e] *= inv;
+    char *dst = static_cast<char *>(P.out) + (((int64_t)qs + j) * H + h) * ROW_BYTES + d0 * 2;
+    if constexpr (DPT == 8) {
+        *reinterpret_cast<uint4 *>(dst) = Tr::pack(acc);
+    } else {
+        float two[8] = {acc[0], acc[1], acc[2], acc[3], 0.f, 0.f, 0.f, 0.f};
+        const uint4 pk = Tr::pack(two);
+        *reinterpret_cast<uint2 *>(dst) = make_uint2(pk.x, pk.y);
+    }
+}
+
+// More than 16 queries per sequence: grid = (sequence, block of 64 queries, head).  The four
+// waves of the workgroup own 16 query columns each and share every K/V tile: the workgroup
+// loads steps of two tiles into LDS together (each thread one 16-byte fragment per tile and
+// array), double-buffered, one barrier per step, with the next step's loads in flight while
+// the current one is computed.  So K/V comes from memory once per 64 queries.
+template <int DT, int B>
+__global__ __launch_bounds__(4 * kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) void pa_multi_block_kernel(
+    const DecodeParams P)
+{
+    using Tr = Traits<DT>;
+    constexpr int W = 4, ROW_BYTES = 256, STEP = 2;
+    constexpr int64_t TILE_BYTES = (int64_t)B * ROW_BYTES;
+    static_assert(DT != PA_F32 && B % kTileTokens == 0, "two-byte elements, whole 16-token tiles per block");
+    constexpr float kUnscale = DT == PA_F16 ? 1.0f / 16384.0f : 1.0f;
+    __shared__ __align__(16) char sm_stage[2][STEP][kTileLds];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int g = lane / 16, c = lane % 16;
+    const int H = P.H;
+    const int h = blockIdx.x % H;
+    const int rest = blockIdx.x / H;
+    const int qb = rest % P.q_blocks;
+    const int s = rest / P.q_blocks;
+    const int n = P.context_lens[s];
+    const int qs = P.q_start[s];
+    const int qlen = P.q_start[s + 1] - qs;
+    const int q0 = qb * 64;
+    if (q0 >= qlen || n <= 0) return;
+    const int wg_members = qlen - q0 < 64 ? qlen - q0 : 64;
+    const int wg_hi = n - qlen + q0 + wg_members;      // tokens the last query of the workgroup sees
+    const int nsteps = (wg_hi + STEP * kTileTokens - 1) / (STEP * kTileTokens);
+    // this wave's 16 columns
+    int members = wg_members - 16 * w;
+    members = members < 0 ? 0 : (members > 16 ? 16 : members);
+    const int t_lo = n - qlen + q0 + 16 * w + 1;
+    const int t_hi = members > 0 ? t_lo + members - 1 : 0;
+
+    QueryCols Q;
+    query_cols_init<DT>(Q, P.q, (int64_t)qs + q0 + 16 * w + c, H, h, c < members, t_lo - 1 + c);
+    const int32_t *__restrict__ table = P.block_tables + (int64_t)s * P.max_blocks;
+
+    // thread (row r16 = tid / 16, column chunk c) moves one fragment of each tile of a step
+    const int r16 = threadIdx.x / 16;
+    uint4 rk[STEP], rv[STEP];
+    auto fetch = [&](int st) {
+#pragma unroll
+        for (int u = 0; u < STEP; ++u) {
+            const int t0 = (st * STEP + u) * kTileTokens;
+            rk[u] = rv[u] = make_uint4(0, 0, 0, 0);
+            if (t0 < wg_hi) {                       // uniform over the workgroup
+                const int pb = table[t0 / B];
+                const int64_t off = ((int64_t)pb * H + h) * TILE_BYTES + (int64_t)(t0 % B + r16) * ROW_BYTES + 16 * c;
+                rk[u] = load16_stream(P.k_cache + off);
+                rv[u] = load16_stream(P.v_cache + off);
+                // rows at or past the context hold no token: zero V, K is masked by the logits
+                if (t0 + r16 >= n) rv[u] = make_uint4(0, 0, 0, 0);
+            }
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < STEP; ++u) {
+            char *kt = sm_stage[buf][u];
+            *reinterpret_cast<uint4 *>(kt + r16 * kKPitch + 16 * c) = rk[u];
+            *reinterpret_cast<uint4 *>(kt + kTileTokens * kKPitch + r16 * kVPitch + 16 * c) = rv[u];
+        }
+    };
+    fetch(0);
+    for (int st = 0; st < nsteps; ++st) {
+        const int buf = st & 1;
+        stash(buf);
+        if (st + 1 < nsteps) fetch(st + 1);
+        // orders this step's LDS writes before their readers, and the reads of two steps ago
+        // (same buffer) before these writes were issued: every wave passed the previous barrier
+        // only after finishing them
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < STEP; ++u) {
+            const int t0 = (st * STEP + u) * kTileTokens;
+            if (t0 < t_hi) {
+                const char *kt = sm_stage[buf][u];
+                tile_step<DT>(Q, kt, kt + kTileTokens * kKPitch, t0, 0xffffu, t0 + kTileTokens > t_lo, P.scale_log2);
+            }
+        }
+    }
+    if (members <= 0) return;
+    const float l = quad_rows_sum(Q.lsum);
+    const float inv = (l > 0.f ? 1.0f / l : 0.f) * kUnscale;
+    if (c < members) {
+        char *dst = static_cast<char *>(P.out) + (((int64_t)qs + q0 + 16 * w + c) * H + h) * ROW_BYTES + 8 * g;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float four[8] = {Q.O[e][0] * inv, Q.O[e][1] * inv, Q.O[e][2] * inv, Q.O[e][3] * inv, 0.f, 0.f, 0.f, 0.f};
+            const uint4 pk = Tr::pack(four);
+            *reinterpret_cast<uint2 *>(dst + 32 * e) = make_uint2(pk.x, pk.y);
+        }
+    }
 }
 
 // One (shared group, head) item of pa_decode_shared.  The blocks that members have in common

@@ -124,3 +124,37 @@ def test_config5_full_cache_beam_step(pa):
     print("cfg5 full: %d blocks, %.0f GB cache, %d copy pairs, worst err %.3g" % (NB, need / 1e9, len(w.copy_pairs), worst))
     del ks, vs
     torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_multi_query_full_shape(pa, dtype):
+    """pa_decode_multi at the shape the benchmark times: 64 sequences x 40 heads, contexts U{1..2048},
+    the last min(ctx, 64) tokens as queries - grids in the thousands of workgroups.  The GPU computes
+    every head; the oracle checks every query row of 5 of the 40 heads (it sees only their slices)."""
+    rng = np.random.default_rng(2000)
+    lens = rng.integers(1, 2049, size=64)
+    w = W.independent_sequences("opt13b_multi_" + dtype, dtype, 40, 128, 16, lens, 2001)
+    v = W.make_values(w)
+    dw = DeviceWorkload(w, v)
+    gpu_cache_ops(pa, dw)
+    kc, vc = oracle_cache_ops(w, v)
+    for qmax in (64, 16):
+        ql = np.minimum(lens, qmax)
+        q_start = np.concatenate([[0], np.cumsum(ql)]).astype(np.int32)
+        T = int(q_start[-1])
+        q = W.to_storage(np.random.default_rng(7).standard_normal((T, 40, 128)).astype(np.float32), dtype)
+        dq = to_dev(q, dtype)
+        out = torch.full_like(dq, float("nan"))
+        pa.pa_decode_multi(out, dq, dw.k_cache, dw.v_cache, dw.block_tables, dw.context_lens, to_dev(q_start),
+                           qmax, 16, float(w.scale), w.max_context_len)
+        torch.cuda.synchronize()
+        got = out_to_f64(out, dtype)
+        assert np.isfinite(got).all()
+        heads = [0, 7, 19, 20, 39]
+        ref = oracle.decode_multi(np.ascontiguousarray(q[:, heads]), np.ascontiguousarray(kc[:, heads]),
+                                  np.ascontiguousarray(vc[:, heads]), w.block_tables, w.context_lens, q_start,
+                                  w.scale, dtype)
+        err = float(np.abs(got[:, heads] - ref).max())
+        print(dtype, "q_len", qmax, "rows", T, "max abs err", err)
+        assert err <= TOL[dtype]

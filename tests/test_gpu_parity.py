@@ -285,6 +285,75 @@ def test_multi_query_decode(pa):
     print("B=64", multi_case(pa, "f16", [500, 130, 64], [20, 130, 1], H=2, B=64))
 
 
+def test_multi_query_every_width(pa):
+    # q_len across the switch from the token-splitting kernel (<= 16 queries) to the 64-query
+    # workgroups, with partly filled last query blocks and contexts shorter than a block of queries
+    lens = [70, 200, 129, 64, 513, 48, 1000, 333]
+    for qmax in (16, 17, 31, 48, 63, 64, 65, 130):
+        q_lens = [min(n, qmax - (i % 3)) for i, n in enumerate(lens)]
+        for dtype in ("f16", "bf16"):
+            print(dtype, qmax, multi_case(pa, dtype, lens, q_lens, H=2, seed=50 + qmax))
+    print("B=128", multi_case(pa, "f16", [700, 130, 128, 129, 5], [100, 130, 16, 1, 5], H=2, B=128, seed=77))
+    print("B=128", multi_case(pa, "bf16", [700, 130, 128, 129, 5], [9, 16, 16, 1, 5], H=2, B=128, seed=78))
+
+
+def test_multi_query_sharp_softmax(pa):
+    # queries scaled by 8: one token dominates, the weights' two 16-bit pieces must carry it
+    for dtype in ("f16", "bf16"):
+        lens = np.array([300, 77, 1200, 16], dtype=np.int64)
+        q_lens = np.array([64, 16, 40, 16], dtype=np.int64)
+        w = W.independent_sequences("multi_sharp", dtype, 2, 128, 16, lens, seed=91)
+        v = W.make_values(w)
+        dw = DeviceWorkload(w, v)
+        gpu_cache_ops(pa, dw)
+        kc, vc = oracle_cache_ops(w, v)
+        q_start = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
+        rng = np.random.default_rng(92)
+        q = W.to_storage(8.0 * rng.standard_normal((int(q_start[-1]), 2, 128)).astype(np.float32), dtype)
+        for qmax, qs in ((64, q_start),):
+            dq = to_dev(q, dtype)
+            out = torch.full_like(dq, float("nan"))
+            pa.pa_decode_multi(out, dq, dw.k_cache, dw.v_cache, dw.block_tables, dw.context_lens, to_dev(qs),
+                               qmax, 16, float(w.scale), w.max_context_len)
+            torch.cuda.synchronize()
+            ref = oracle.decode_multi(q, kc, vc, w.block_tables, w.context_lens, qs, w.scale, dtype)
+            err = float(np.abs(out_to_f64(out, dtype) - ref).max())
+            assert err <= TOL[dtype], "sharp multi %s: %g" % (dtype, err)
+
+
+def test_multi_query_one_hot_operands_fail_by_position(pa):
+    # K, V and Q made of single ones: every logit is 0 or 1 and every output element is a
+    # small rational that names the (query, token, dimension) it came from, so a slip in an
+    # MFMA operand or LDS layout shows up at the position it happens
+    for dtype in ("f16", "bf16"):
+        for q_len in (16, 64):
+            n, H, D, B = 96, 2, 128, 16
+            w = W.independent_sequences("onehot", dtype, H, D, B, np.array([n]), seed=3)
+            kc = np.zeros(w.cache_shape(), dtype=np.float32)
+            vc = np.zeros(w.cache_shape(), dtype=np.float32)
+            q = np.zeros((q_len, H, D), dtype=np.float32)
+            for t in range(n):
+                pb, off = int(w.block_tables[0, t // B]), t % B
+                for h in range(H):
+                    kc[pb, h, off, (5 * t + 3 * h) % D] = 1.0          # token t's key: one dimension
+                    vc[pb, h, off, (7 * t + h) % D] = 1.0 + (t % 5)    # its value: another one
+            for i in range(q_len):
+                for h in range(H):
+                    q[i, h, (5 * (n - q_len + i - 2 * (i % 7)) + 3 * h) % D] = 4.0   # picks one earlier token
+                    q[i, h, (11 * i + 1) % D] += 2.0
+            kcs, vcs, qs_ = W.to_storage(kc, dtype), W.to_storage(vc, dtype), W.to_storage(q, dtype)
+            q_start = np.array([0, q_len], dtype=np.int32)
+            out = torch.full((q_len, H, D), float("nan"), dtype=torch.float16 if dtype == "f16" else torch.bfloat16,
+                             device="cuda")
+            pa.pa_decode_multi(out, to_dev(qs_, dtype), to_dev(kcs, dtype), to_dev(vcs, dtype), to_dev(w.block_tables),
+                               to_dev(w.context_lens), to_dev(q_start), q_len, B, 1.0, n)
+            torch.cuda.synchronize()
+            ref = oracle.decode_multi(qs_, kcs, vcs, w.block_tables, w.context_lens, q_start, 1.0, dtype)
+            got = out_to_f64(out, dtype)
+            bad = np.argwhere(np.abs(got - ref) > TOL[dtype])
+            assert len(bad) == 0, "%s q_len %d: first mismatches at (query, head, dim) %s" % (dtype, q_len, bad[:8].tolist())
+
+
 def test_multi_query_of_one_equals_decode(pa):
     w = W.config2(seed=13, num_seqs=12, max_len=600, H=4)
     v = W.make_values(w)
