@@ -24,6 +24,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+MFMA_F16_PEAK = 2.5e15          # MI355X published dense f16/bf16 matrix peak, flop/s
 
 
 def parse():
@@ -57,6 +58,8 @@ def parse():
                          "layer cache write + decode")
     ap.add_argument("--multi-query", action="store_true",
                     help="instead of the step benchmark: pa_decode_multi at the OPT-13B shape for several q_len")
+    ap.add_argument("--q-lens", default="1,4,16,64,256",
+                    help="--multi-query: the q_len values to run, comma separated")
     ap.add_argument("--paging-overhead", action="store_true",
                     help="instead of the step benchmark: pa_decode over randomly placed blocks against the same "
                          "sequences stored contiguously (the axis of the paper's kernel microbenchmark, Sec. 7.1)")
@@ -269,9 +272,11 @@ def cfg5_full_step(pa, W, np, torch, dev, steps):
     print(json.dumps(res))
 
 
-def multi_query(pa, W, np, torch, dev):
-    """pa_decode_multi at the OPT-13B layer shape: every sequence brings its last q_len tokens as queries.
-    K/V of a sequence is read once per block of 16 queries, so KV bytes = sum_s ceil(q_len_s/16)*ctx_s*H*2*D*E."""
+def multi_query(pa, W, np, torch, dev, q_lens=(1, 4, 16, 64, 256)):
+    """pa_decode_multi at the OPT-13B layer shape: every sequence brings its last min(ctx, q_len) tokens as
+    queries.  Per row a roofline: algorithmic bytes = K and V of every cached token once + q in + out;
+    algorithmic flops = 4*D per (query, visible token) pair (both products, causal).  The bound is the one
+    that takes longer at the published peaks (HBM 8 TB/s, dense f16 MFMA 2.5 PFLOP/s)."""
     rng = np.random.default_rng(2000)
     lens = rng.integers(1, 2049, size=64)
     w = W.independent_sequences("opt13b_multi", "f16", 40, 128, 16, lens, 2001)
@@ -281,7 +286,7 @@ def multi_query(pa, W, np, torch, dev):
     bt = torch.from_numpy(w.block_tables).to(dev)
     cl = torch.from_numpy(w.context_lens).to(dev)
     rows = []
-    for qmax in (1, 4, 16, 64, 256):
+    for qmax in q_lens:
         ql = np.minimum(lens, qmax)
         qs = np.concatenate([[0], np.cumsum(ql)]).astype(np.int32)
         T = int(qs[-1])
@@ -290,9 +295,19 @@ def multi_query(pa, W, np, torch, dev):
         dqs = torch.from_numpy(qs).to(dev)
         us = _time_us(lambda: pa.pa_decode_multi(out, q, kc, vc, bt, cl, dqs, qmax, B, float(w.scale),
                                                  w.max_context_len), 50, torch)
-        kv = int((((ql + 15) // 16) * lens).sum()) * H * D * 2 * 2
+        algo_bytes = w.kv_bytes_logical() + 2 * T * H * D * 2
+        pairs = int((ql * lens - ql * (ql - 1) // 2).sum())          # query i of q_len sees ctx - q_len + i + 1 tokens
+        flops = 4 * D * pairs * H
+        t_hbm, t_mfma = algo_bytes / (HBM_PEAK_GBPS * 1e9), flops / MFMA_F16_PEAK
+        if t_hbm >= t_mfma:
+            roof = {"bound": "hbm", "achieved": algo_bytes / us / 1e3, "peak": HBM_PEAK_GBPS, "unit": "GB/s"}
+        else:
+            roof = {"bound": "mfma", "achieved": flops / us / 1e6, "peak": MFMA_F16_PEAK / 1e12, "unit": "TFLOP/s"}
+        roof["frac"] = roof["achieved"] / roof["peak"]
         rows.append({"max_q_len": qmax, "query_tokens": T, "us": us, "query_tokens_per_s": T / us * 1e6,
-                     "kv_GBps": kv / us / 1e3})
+                     "algorithmic_bytes": algo_bytes, "algorithmic_flops": flops,
+                     "hbm_frac": algo_bytes / us / 1e3 / HBM_PEAK_GBPS, "mfma_frac": flops / us / 1e6 / (MFMA_F16_PEAK / 1e12),
+                     "roofline": roof})
     q1 = torch.randn((64, H, D), dtype=torch.float16, device=dev)
     o1 = torch.empty_like(q1)
     us = _time_us(lambda: pa.pa_decode(o1, q1, kc, vc, bt, cl, B, float(w.scale), w.max_context_len, 0, None),
@@ -373,7 +388,7 @@ def main():
     if args.shared_prefix:
         return shared_prefix(pa, W, np, torch, dev)
     if args.multi_query:
-        return multi_query(pa, W, np, torch, dev)
+        return multi_query(pa, W, np, torch, dev, tuple(int(x) for x in args.q_lens.split(",")))
     if args.cfg5_full_step:
         return cfg5_full_step(pa, W, np, torch, dev, min(args.steps, 10))
 

@@ -251,8 +251,15 @@ template <int DT, int B>
 void launch_multi_b(const DecodeArgs &a, int max_q_len)
 {
     if (max_q_len <= 16) {
-        hipLaunchKernelGGL((pa_multi_split_kernel<DT, B, 8>), dim3((unsigned)a.p.S * (unsigned)a.p.H), dim3(8 * kWave), 0,
-                           a.stream, a.p);
+        // waves per item as in the single-query kernel: sixteen stream long contexts fastest (OPT-13B
+        // shape, 64 sequences of up to 2048 tokens: 178 us against 185 us with eight)
+        const dim3 grid((unsigned)a.p.S * (unsigned)a.p.H);
+        if (a.waves >= 16)
+            hipLaunchKernelGGL((pa_multi_split_kernel<DT, B, 16>), grid, dim3(16 * kWave), 0, a.stream, a.p);
+        else if (a.waves >= 8)
+            hipLaunchKernelGGL((pa_multi_split_kernel<DT, B, 8>), grid, dim3(8 * kWave), 0, a.stream, a.p);
+        else
+            hipLaunchKernelGGL((pa_multi_split_kernel<DT, B, 4>), grid, dim3(4 * kWave), 0, a.stream, a.p);
     } else {
         const unsigned blocks = (unsigned)a.p.S * (unsigned)a.p.q_blocks * (unsigned)a.p.H;
         hipLaunchKernelGGL((pa_multi_block_kernel<DT, B>), dim3(blocks), dim3(4 * kWave), 0, a.stream, a.p);
@@ -518,6 +525,7 @@ pa_status pa_decode_multi(void *out, const void *q, const void *k_cache, const v
                 num_heads, scale, stream);
     a.p.q_start = q_start;
     a.p.q_blocks = (int32_t)q_blocks;
+    a.waves = waves_for(max_context_len, kTileTokens);
     const bool ok = dtype == PA_F16 ? launch_multi<PA_F16>(a, block_size, max_q_len)
                                     : launch_multi<PA_BF16>(a, block_size, max_q_len);
     if (!ok) return PA_ERR_UNSUPPORTED;

@@ -165,6 +165,7 @@ template <> struct Traits<PA_BF16> {
 };
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
 // 16-byte load with the non-temporal hint: K/V bytes are used exactly once per
 // call, and streaming them past the caches measurably raises the HBM rate.

@@ -601,27 +601,32 @@ __global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))
     char *const kt = sm_region[w];
     char *const vt = kt + kTileTokens * kKPitch;
 
-    auto base_of = [&](int ti) -> int64_t {
-        const int t0 = ti * kTileTokens;
-        const int pb = table[t0 / B];            // wave-uniform: a scalar load
-        return ((int64_t)pb * H + h) * TILE_BYTES + (int64_t)(t0 % B) * ROW_BYTES;
+    // block ids are looked up two tiles ahead (wave-uniform scalar loads), tiles fetched one ahead
+    auto block_of = [&](int ti) -> int { return ti < ntiles ? table[ti * kTileTokens / B] : 0; };
+    auto base_of = [&](int ti, int pb) -> int64_t {
+        return ((int64_t)pb * H + h) * TILE_BYTES + (int64_t)(ti * kTileTokens % B) * ROW_BYTES;
     };
     TileRegs R;
-    if (w < ntiles) tile_fetch(R, P.k_cache, P.v_cache, base_of(w));
+    if (w < ntiles) tile_fetch(R, P.k_cache, P.v_cache, base_of(w, block_of(w)));
+    int pb_next = block_of(w + W);
     for (int ti = w; ti < ntiles; ti += W) {
         const int t0 = ti * kTileTokens;
         // masking starts where the tile reaches past what the first query sees
         const bool check = t0 + kTileTokens > t_lo;
         tile_store(R, kt, vt, t_hi - t0, check);
-        if (ti + W < ntiles) tile_fetch(R, P.k_cache, P.v_cache, base_of(ti + W));
+        if (ti + W < ntiles) tile_fetch(R, P.k_cache, P.v_cache, base_of(ti + W, pb_next));
+        pb_next = block_of(ti + 2 * W);
         __builtin_amdgcn_wave_barrier();
         tile_step<DT>(Q, kt, vt, t0, 0xffffu, check, P.scale_log2);
         __builtin_amdgcn_wave_barrier();
     }
     Q.lsum = quad_rows_sum(Q.lsum);
 
-    // merge the waves: each leaves its 16 x 128 partial sums in its own region
-    float(*const mine)[D] = reinterpret_cast<float(*)[D]>(sm_region[w]);
+    // merge the waves: each leaves its 16 x 128 partial sums in its own region (rows 16 bytes
+    // apart from a multiple of the bank count, so the 16 queries of one store spread out)
+    constexpr int MROW = D + 4;
+    static_assert(16 * MROW * 4 <= kTileLds, "partial sums fit the staging region");
+    float(*const mine)[MROW] = reinterpret_cast<float(*)[MROW]>(sm_region[w]);
 #pragma unroll
     for (int e = 0; e < 8; ++e)
         *reinterpret_cast<float4 *>(&mine[c][16 * e + 4 * g]) =
@@ -633,7 +638,7 @@ __global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))
     __syncthreads();
     constexpr int TPQ = W * kWave / 16;     // threads per query row
     constexpr int DPT = D / TPQ;            // output dimensions per thread: 4 (eight waves) or 8 (four)
-    static_assert(DPT == 4 || DPT == 8, "workgroup width");
+    static_assert(DPT == 2 || DPT == 4 || DPT == 8, "workgroup width");
     const int j = threadIdx.x / TPQ, d0 = (threadIdx.x % TPQ) * DPT;
     if (j >= members) return;
     float M = sm_m[0][j];
@@ -646,7 +651,7 @@ __global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))
     for (int i = 0; i < W; ++i) {
         const float f = __builtin_amdgcn_exp2f(sm_m[i][j] - M);
         l = __builtin_fmaf(sm_l[i][j], f, l);
-        const float *src = &reinterpret_cast<const float(*)[D]>(sm_region[i])[j][d0];
+        const float *src = &reinterpret_cast<const float(*)[MROW]>(sm_region[i])[j][d0];
 #pragma unroll
         for (int e = 0; e < DPT; ++e) acc[e] = __builtin_fmaf(src[e], f, acc[e]);
     }
@@ -654,12 +659,19 @@ __global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))
 #pragma unroll
     for (int e = 0; e < DPT; ++e) acc[e] *= inv;
     char *dst = static_cast<char *>(P.out) + (((int64_t)qs + j) * H + h) * ROW_BYTES + d0 * 2;
+    // Output rows are written with the streaming hint: on this device small writes in the middle of
+    // a read stream cost several times their size in read bandwidth (a 256-byte row per 32 KiB read
+    // slows a pure streaming kernel by 13%), and least so when they bypass the caches.
     if constexpr (DPT == 8) {
-        *reinterpret_cast<uint4 *>(dst) = Tr::pack(acc);
+        store_frag_stream(reinterpret_cast<uint4 *>(dst), __builtin_bit_cast(u32x4_t, Tr::pack(acc)));
+    } else if constexpr (DPT == 4) {
+        float half_row[8] = {acc[0], acc[1], acc[2], acc[3], 0.f, 0.f, 0.f, 0.f};
+        const uint4 pk = Tr::pack(half_row);
+        const u32x2_t two = {pk.x, pk.y};
+        __builtin_nontemporal_store(two, reinterpret_cast<u32x2_t *>(dst));
     } else {
-        float two[8] = {acc[0], acc[1], acc[2], acc[3], 0.f, 0.f, 0.f, 0.f};
-        const uint4 pk = Tr::pack(two);
-        *reinterpret_cast<uint2 *>(dst) = make_uint2(pk.x, pk.y);
+        float pair[8] = {acc[0], acc[1], 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        __builtin_nontemporal_store(Tr::pack(pair).x, reinterpret_cast<uint32_t *>(dst));
     }
 }
 
@@ -749,16 +761,29 @@ __global__ __launch_bounds__(4 * kWave) __attribute__((amdgpu_waves_per_eu(4, 8)
             }
         }
     }
+    // finished rows: through the wave's share of the (now idle) staging buffers, so that every store
+    // instruction writes whole 256-byte rows
+    __syncthreads();                                   // all waves are done reading the tiles
     if (members <= 0) return;
     const float l = quad_rows_sum(Q.lsum);
     const float inv = (l > 0.f ? 1.0f / l : 0.f) * kUnscale;
-    if (c < members) {
-        char *dst = static_cast<char *>(P.out) + (((int64_t)qs + q0 + 16 * w + c) * H + h) * ROW_BYTES + 8 * g;
+    constexpr int MROW = 128 + 4;
+    static_assert(W * 16 * MROW * 4 <= 2 * STEP * kTileLds, "output rows fit the staging buffers");
+    float(*const rows)[MROW] = reinterpret_cast<float(*)[MROW]>(&sm_stage[0][0][0] + w * 16 * MROW * 4);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float four[8] = {Q.O[e][0] * inv, Q.O[e][1] * inv, Q.O[e][2] * inv, Q.O[e][3] * inv, 0.f, 0.f, 0.f, 0.f};
-            const uint4 pk = Tr::pack(four);
-            *reinterpret_cast<uint2 *>(dst + 32 * e) = make_uint2(pk.x, pk.y);
+    for (int e = 0; e < 8; ++e)
+        *reinterpret_cast<float4 *>(&rows[c][16 * e + 4 * g]) =
+            make_float4(Q.O[e][0] * inv, Q.O[e][1] * inv, Q.O[e][2] * inv, Q.O[e][3] * inv);
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int j = g + 4 * i;                        // lane 16g + c: dimensions 8c .. 8c+7 of query j
+        if (j < members) {
+            float v8[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v8[e] = rows[j][8 * c + e];
+            char *dst = static_cast<char *>(P.out) + (((int64_t)qs + q0 + 16 * w + j) * H + h) * ROW_BYTES + 16 * c;
+            store_frag_stream(reinterpret_cast<uint4 *>(dst), __builtin_bit_cast(u32x4_t, Tr::pack(v8)));
         }
     }
 }
