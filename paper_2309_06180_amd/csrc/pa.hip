@@ -92,7 +92,6 @@ struct DecodeArgs {
     DecodeParams p;
     int32_t waves;   // wavefronts per workgroup
     int32_t steps;   // pa_decode_shared only: which of SHARED_PLAN, SHARED_DECODE to enqueue
-    bool long_lists; // pa_decode_shared only: contexts beyond 2048 tokens
     hipStream_t stream;
 };
 
@@ -108,37 +107,26 @@ void launch_decode_kernel(const DecodeArgs &a, unsigned items)
 
 enum PlanMode { PLAN_SINGLE = 0, PLAN_PART = 1, PLAN_SHARED = 2 };
 
-// pa_decode_shared: group discovery, tile lists, then one launch with the shared groups on the
-// matrix cores and everything else on the ordinary one-pass kernel
+// pa_decode_shared: the sharing plan (group discovery and tile lists, one launch), then one launch
+// with the groups on the matrix cores and everything else on the ordinary one-pass kernel
 template <int DT, int D, int B>
 void launch_shared(const DecodeArgs &a)
 {
     if constexpr (DT != PA_F32 && D == 128 && B % 16 == 0) {
         const unsigned S = (unsigned)a.p.S;
-        // a shared group has two or more members: at most S/2 groups
-        const unsigned max_groups = (S + 1) / 2;
-        if (a.steps & SHARED_PLAN) {
-            hipLaunchKernelGGL(find_groups_kernel, dim3(1), dim3(kGroupThreads), 0, a.stream, a.p.block_tables,
-                               a.p.max_blocks, a.p.context_lens, a.p.S, B, kGroupMaxMfma,
-                               const_cast<int32_t *>(a.p.ginfo));
-            hipLaunchKernelGGL(build_tiles_kernel, dim3((max_groups + kTileWaves - 1) / kTileWaves),
-                               dim3(kTileWaves * kWave), 0, a.stream, a.p.block_tables, a.p.max_blocks,
-                               a.p.context_lens, a.p.S, B, const_cast<int32_t *>(a.p.ginfo),
-                               const_cast<int2 *>(a.p.tiles));
-        }
+        if (a.steps & SHARED_PLAN)
+            hipLaunchKernelGGL(shared_plan_kernel, dim3(kPlanBlocks), dim3(kPlanThreads), 0, a.stream, a.p.block_tables,
+                               a.p.max_blocks, a.p.context_lens, a.p.S, B, const_cast<int32_t *>(a.p.ginfo),
+                               const_cast<int4 *>(a.p.tiles));
         if (!(a.steps & SHARED_DECODE)) return;
-        DecodeArgs f = a;
-        f.p.group_blocks = (int32_t)(max_groups * (unsigned)a.p.H);
-        const unsigned blocks = (unsigned)f.p.group_blocks + S * (unsigned)a.p.H;
-        // A group item walks up to (members x context / 16) tiles.  Past 2048 tokens of context
-        // that chain, at eight waves, is a large part of the whole launch, and the last items
-        // to start decide when the launch ends: sixteen waves per item halve it.
-        if (a.waves >= 16 && a.long_lists)
-            hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 16>), dim3(blocks), dim3(16 * kWave), 0, a.stream, f.p);
+        // groups + singles <= S: one workgroup per (sequence, head) always suffices
+        const dim3 grid(S * (unsigned)a.p.H);
+        if (a.waves >= 16)
+            hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 16>), grid, dim3(16 * kWave), 0, a.stream, a.p);
         else if (a.waves >= 8)
-            hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 8>), dim3(blocks), dim3(8 * kWave), 0, a.stream, f.p);
+            hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 8>), grid, dim3(8 * kWave), 0, a.stream, a.p);
         else
-            hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 4>), dim3(blocks), dim3(4 * kWave), 0, a.stream, f.p);
+            hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 4>), grid, dim3(4 * kWave), 0, a.stream, a.p);
     }
 }
 
@@ -295,10 +283,10 @@ void fill_common(DecodeArgs &a, void *out, const void *q, const void *k_cache, c
     a.stream = static_cast<hipStream_t>(stream);
 }
 
-bool shared_on_matrix_cores(pa_dtype dtype, int32_t head_dim, int32_t block_size, int32_t max_blocks)
+bool shared_on_matrix_cores(pa_dtype dtype, int32_t head_dim, int32_t block_size, int32_t num_seqs)
 {
-    // tile-list entries keep the logical block index in 15 bits
-    return dtype != PA_F32 && head_dim == 128 && block_size % 16 == 0 && max_blocks <= 32768;
+    // the planning kernel keeps its scan state for the whole batch in LDS
+    return dtype != PA_F32 && head_dim == 128 && block_size % 16 == 0 && num_seqs <= kPlanMaxSeqs;
 }
 
 size_t ginfo_bytes(int32_t S) { return (ginfo_words(S) * sizeof(int32_t) + 15) & ~(size_t)15; }
@@ -416,7 +404,7 @@ size_t pa_decode_shared_workspace_bytes(int32_t num_seqs, int32_t num_heads, int
                                         int32_t max_blocks_per_seq)
 {
     if (num_seqs <= 0 || num_heads <= 0 || head_dim <= 0 || max_blocks_per_seq <= 0) return 0;
-    return ginfo_bytes(num_seqs) + (size_t)num_seqs * max_blocks_per_seq * sizeof(int2);
+    return ginfo_bytes(num_seqs) + (size_t)num_seqs * max_blocks_per_seq * sizeof(int4);
 }
 
 static pa_status decode_shared_steps(int steps, void *out, const void *q, const void *k_cache,
@@ -439,7 +427,7 @@ static pa_status decode_shared_steps(int steps, void *out, const void *q, const 
         (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)))
         return PA_ERR_ALIGN;
     if ((int64_t)num_seqs * num_heads > (int64_t)0x7fffffff / 64) return PA_ERR_SHAPE;
-    if (!shared_on_matrix_cores(dtype, head_dim, block_size, max_blocks_per_seq)) {
+    if (!shared_on_matrix_cores(dtype, head_dim, block_size, num_seqs)) {
         // no several-query kernel for this shape: nothing to plan, and the plain one-pass
         // kernel gives the same result
         if (!(steps & SHARED_DECODE)) return PA_OK;
@@ -457,10 +445,9 @@ static pa_status decode_shared_steps(int steps, void *out, const void *q, const 
                 num_heads, scale, stream);
     a.p.max_parts = 1;
     a.steps = steps;
-    a.long_lists = max_context_len > 2048;
     a.waves = waves_for(max_context_len, chunk_tokens(dtype, head_dim, block_size));
     a.p.ginfo = static_cast<const int32_t *>(workspace);
-    a.p.tiles = reinterpret_cast<const int2 *>(static_cast<const char *>(workspace) + ginfo_bytes(num_seqs));
+    a.p.tiles = reinterpret_cast<const int4 *>(static_cast<const char *>(workspace) + ginfo_bytes(num_seqs));
     if (!dispatch_decode(a, dtype, head_dim, block_size, PLAN_SHARED)) return PA_ERR_UNSUPPORTED;
     return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
 }

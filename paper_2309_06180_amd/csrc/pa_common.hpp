@@ -18,14 +18,11 @@ constexpr int kWave = 64;
 // schedules the loads just in time whatever the source says (a few in flight per wave, the
 // rest of the latency is covered by the other resident waves), and measured on MI355X that is
 // what the memory side likes: one chunk per trip is as fast as two at the OPT-13B shape
-// (170 us) and 2% faster at configs 4 and 5; four per trip is slower everywhere.  Inside a
-// shared group's item, where a member has only a few of the workgroup's waves, two per trip
-// win (config 5: 383 against 405 us), and so they do in the split-context kernel (config 4
-// at 512-token partitions: 194 against 201 us).
+// (170 us) and 2% faster at configs 4 and 5; four per trip is slower everywhere.  In the
+// split-context kernel, where fewer waves work on one range, two per trip win (config 4 at
+// 512-token partitions: 194 against 201 us).
 constexpr int kChunksPerTrip = 1;
 constexpr int kPartChunksPerTrip = 2;
-constexpr int kGroupChunksPerTrip = 2;
-constexpr int kGroupMaxMfma = 8;   // members of a shared group (of the 16 query rows of the MFMA tiles)
 constexpr float kLog2e = 1.4426950408889634f;
 // running-maximum start value: finite, so that (m - m) is 0 and never NaN
 constexpr float kNegBig = -3.0e38f;

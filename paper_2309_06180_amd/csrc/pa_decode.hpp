@@ -34,31 +34,44 @@ struct DecodeParams {
     const char *k_cache, *v_cache;
     const int32_t *block_tables;
     const int32_t *context_lens;
-    const int32_t *ginfo;   // group table built by find_groups_kernel (pa_decode_shared)
-    const int2 *tiles;      // per-group tile lists built by build_tiles_kernel
+    const int32_t *ginfo;   // sharing plan of pa_decode_shared: group table (find_groups_kernel)
+    const int4 *tiles;      // sharing plan: per-group tile lists (build_tiles_kernel)
     const int32_t *q_start; // multi-query path: first query row of every sequence, [S+1]
     float *ws_acc, *ws_ml;
     int32_t max_blocks, S, H;
     int32_t partition_size, max_parts;
-    int32_t group_blocks;    // fused shared launch: workgroups [0, group_blocks) are group items
-    int32_t q_blocks;        // multi-query path: blocks of 16 queries per sequence in the grid
+    int32_t q_blocks;        // multi-query path: blocks of 64 queries per sequence in the grid
     float scale_log2;
 };
 
-// Layout of the group table of pa_decode_shared, arrays of S int32 entries:
-// in_group[s] (1 if s belongs to a group of two or more), group_size[s] (members
-// of the group that starts at sequence s, 0 if none starts there), tile_count[s]
-// (entries of that group's tile list), adj[s] (scratch of the discovery),
-// own_start[s] (for a member of a group: the token position from which it reads its
-// blocks itself; everything before is on the group's tile list), the compact list of
-// the first sequences of shared groups, and its length.
+// Sharing plan of pa_decode_shared.  The group table is 6 arrays of S int32 entries followed by
+// two counters:
+//   in_group[s]      1 if sequence s belongs to a group (two or more members), else 0
+//   group_size[s]    members of the group whose first sequence is s (consecutive sequences
+//                    s .. s + size - 1); 0 if no group starts at s
+//   tile_count[s]    entries on the tile list of the group that starts at s (written only where a
+//                    group starts; elsewhere undefined)
+//   adj[s]           leading full blocks that s maps to the same physical blocks as s - 1
+//   single_list[i]   the sequences outside any group, ascending, i < single_count
+//   group_list[i]    first sequences of the groups, ascending, i < group_count
+//   group_count, single_count
+// The tile list of the group that starts at s begins at entry s * max_blocks of the tile array
+// (a group's members own that many entries between them).  It holds every physical block
+// that a member maps, once per logical position, ordered by position:
+//   x  physical block id
+//   y  bits 0..15: members (bit j = sequence s + j) that map this block at this position;
+//      bit 16: some member in the set sees only part of the tokens stored
+//   z  logical block index (position / block_size)
+//   w  tokens of the block that the longest member of the set sees (1 .. block_size)
+constexpr int kGroupMax = 16;    // members of a group: one query column of the MFMA tiles each
 __device__ __host__ __forceinline__ int ginfo_in_group(int S, int s) { (void)S; return s; }
 __device__ __host__ __forceinline__ int ginfo_group_size(int S, int s) { return S + s; }
 __device__ __host__ __forceinline__ int ginfo_tile_count(int S, int s) { return 2 * S + s; }
 __device__ __host__ __forceinline__ int ginfo_adj(int S, int s) { return 3 * S + s; }
-__device__ __host__ __forceinline__ int ginfo_own_start(int S, int s) { return 4 * S + s; }
-__device__ __host__ __forceinline__ int ginfo_shared_list(int S, int i) { return 5 * S + i; }
-__device__ __host__ __forceinline__ int ginfo_shared_count(int S) { return 6 * S; }
+__device__ __host__ __forceinline__ int ginfo_single_list(int S, int i) { return 4 * S + i; }
+__device__ __host__ __forceinline__ int ginfo_group_list(int S, int i) { return 5 * S + i; }
+__device__ __host__ __forceinline__ int ginfo_group_count(int S) { return 6 * S; }
+__device__ __host__ __forceinline__ int ginfo_single_count(int S) { return 6 * S + 1; }
 __device__ __host__ __forceinline__ size_t ginfo_words(int S) { return 6 * (size_t)S + 4; }
 
 // A sixteen-wave workgroup is kept alone on its compute unit (at most 7 waves
@@ -262,7 +275,7 @@ __device__ __forceinline__ void decode_range(const DecodeParams &P, const int s,
 // One work item of the decode kernel: a (sequence, head) over its whole context, or over one
 // fixed-size partition of it.
 template <int DT, int D, int B, int W, int U, int MODE>
-__device__ __forceinline__ void decode_body(const DecodeParams &P, const int block_index)
+__device__ __forceinline__ void decode_body(const DecodeParams &P, const int s, const int h, const int part)
 {
     using Tr = Traits<DT>;
     constexpr int EPL = Tr::EPL;
@@ -272,13 +285,6 @@ __device__ __forceinline__ void decode_body(const DecodeParams &P, const int blo
     const int g = lane / LPT;
     const int c = lane % LPT;
     const int H = P.H;
-
-    int item = block_index;
-    const int h = item % H;
-    item /= H;
-    const int part = MODE == MODE_PART ? item % P.max_parts : 0;
-    const int s = MODE == MODE_PART ? item / P.max_parts : item;
-
     const int n = P.context_lens[s];
     const int t_begin = MODE == MODE_PART ? part * P.partition_size : 0;
     const int t_end = MODE == MODE_PART ? (t_begin + P.partition_size < n ? t_begin + P.partition_size : n) : n;
@@ -313,7 +319,13 @@ __device__ __forceinline__ void decode_body(const DecodeParams &P, const int blo
 template <int DT, int D, int B, int W, int U, int MODE>
 __global__ __launch_bounds__(W *kWave) PA_OCC_ATTR void pa_decode_kernel(const DecodeParams P)
 {
-    decode_body<DT, D, B, W, U, MODE>(P, (int)blockIdx.x);
+    // grid index: head fastest, then partition, then sequence
+    int item = (int)blockIdx.x;
+    const int h = item % P.H;
+    item /= P.H;
+    const int part = MODE == MODE_PART ? item % P.max_parts : 0;
+    const int s = MODE == MODE_PART ? item / P.max_parts : item;
+    decode_body<DT, D, B, W, U, MODE>(P, s, h, part);
 }
 
 // Merge of the split-context partials: out = sum_p 2^(m_p-M) a_p / sum_p 2^(m_p-M) l_p

@@ -84,3 +84,51 @@ def gpu_decode_shared(pa, dw: DeviceWorkload) -> torch.Tensor:
                         float(w.scale), w.max_context_len, ws)
     torch.cuda.synchronize()
     return out
+
+
+def mixed_sharing_workload(dtype: str) -> W.Workload:
+    """Sharing patterns side by side: three forks that have not diverged (every block shared, the partial
+    last one included), a loner, a parent and four children that grew by different amounts, a pair with
+    exactly one full block in common, ten forks of one prompt, forty forks of another."""
+    from harness.blocks import BlockManager
+    rng = np.random.default_rng(33)
+    B, NB, H, D = 16, 1400, 2, 128
+    mgr = BlockManager(NB, B, order=rng.permutation(NB))
+    seqs = []
+    a = mgr.allocate(70)
+    seqs += [a, mgr.fork(a), mgr.fork(a)]                     # identical: 4 full blocks + 6 tokens
+    seqs.append(mgr.allocate(33))                             # loner
+    b = mgr.allocate(200)
+    kids = [mgr.fork(b) for _ in range(4)]
+    grow = [0, 5, 40, 90, 17]
+    for sq, gsteps in zip([b] + kids, grow):
+        for _ in range(gsteps):
+            mgr.append(sq)
+    seqs += [b] + kids
+    c = mgr.allocate(16)
+    seqs += [c, mgr.fork(c)]                                  # exactly one shared full block, nothing else
+    d = mgr.allocate(150)
+    many = [d] + [mgr.fork(d) for _ in range(9)]
+    for i, sq in enumerate(many):
+        for _ in range(3 * i):
+            mgr.append(sq)
+    seqs += many
+    e = mgr.allocate(260)
+    crowd = [e] + [mgr.fork(e) for _ in range(39)]
+    for i, sq in enumerate(crowd):
+        for _ in range((7 * i) % 45):
+            mgr.append(sq)
+    seqs += crowd
+    mgr.take_copies()
+    filled = np.zeros((NB, B), dtype=bool)
+    for sq in seqs:
+        for j, pb in enumerate(sq.blocks):
+            filled[pb, : min(B, sq.length - j * B)] = True
+    mb = max(len(sq.blocks) for sq in seqs) + 1
+    bt = np.full((len(seqs), mb), -1, dtype=np.int32)
+    for i, sq in enumerate(seqs):
+        bt[i, : len(sq.blocks)] = sq.blocks
+    return W.Workload("mixed", dtype, H, D, B, NB, np.float32(1 / np.sqrt(D)), bt,
+                      np.array([sq.length for sq in seqs], dtype=np.int32), filled,
+                      np.zeros((0, 2), dtype=np.int64), np.zeros(0, dtype=np.int64),
+                      np.zeros(len(seqs), dtype=np.int64), seed=34)

@@ -20,7 +20,7 @@ def pa():
 
 
 from gpu_util import (TOL, DeviceWorkload, gpu_cache_ops, gpu_decode, gpu_decode_shared,  # noqa: E402
-                      oracle_cache_ops, out_to_f64, same_bits, to_dev, to_np)
+                      mixed_sharing_workload, oracle_cache_ops, out_to_f64, same_bits, to_dev, to_np)
 
 
 SHARED = "shared"     # pseudo partition value: run pa_decode_shared
@@ -133,10 +133,10 @@ def test_shared_decode_parallel_sampling(pa):
 
 
 def test_shared_decode_beam_groups_of_six(pa):
-    # groups larger than the kernel's query slots are split; beams share 55% of their blocks
+    # beams share 55% of their blocks
     w = W.config5(num_seqs=20, H=3, min_len=100, max_len=900)
     print(run_and_compare(pa, w, partitions=(SHARED, 0)))
-    # contexts past 2048 tokens: group items run with sixteen waves
+    # contexts past 2048 tokens
     w = W.config5(seed=5007, num_seqs=8, H=2, min_len=1800, max_len=2400)
     assert w.max_context_len > 2048
     print(run_and_compare(pa, w, partitions=(SHARED,)))
@@ -150,7 +150,7 @@ def test_shared_decode_large_batch(pa):
 
 
 def test_shared_decode_without_sharing(pa):
-    # nothing in common: every sequence is a group of one and only the suffix path runs
+    # nothing in common: no group forms, every sequence goes through the one-pass items
     for dtype, D in (("f16", 128), ("bf16", 128), ("f32", 64)):
         rng = np.random.default_rng(31)
         lens = np.concatenate([rng.integers(1, 500, size=9), [0, 1, 16]])
@@ -160,45 +160,23 @@ def test_shared_decode_without_sharing(pa):
 
 def test_shared_decode_fully_shared_and_mixed(pa):
     # forks that have not diverged (every block shared, the partial last one included), a group
-    # whose members share different numbers of blocks, a loner in between, and a group of 5
-    from harness.blocks import BlockManager
-    rng = np.random.default_rng(33)
-    B, NB, H, D = 16, 400, 2, 128
-    mgr = BlockManager(NB, B, order=rng.permutation(NB))
-    seqs = []
-    a = mgr.allocate(70)
-    seqs += [a, mgr.fork(a), mgr.fork(a)]                     # identical: 4 full blocks + 6 tokens
-    seqs.append(mgr.allocate(33))                             # loner
-    b = mgr.allocate(200)
-    kids = [mgr.fork(b) for _ in range(4)]
-    grow = [0, 5, 40, 90, 17]
-    for sq, gsteps in zip([b] + kids, grow):
-        for _ in range(gsteps):
-            mgr.append(sq)
-    seqs += [b] + kids                                        # group of 5 -> 4 + 1
-    c = mgr.allocate(16)
-    seqs += [c, mgr.fork(c)]                                  # exactly one shared full block, nothing else
-    d = mgr.allocate(150)
-    many = [d] + [mgr.fork(d) for _ in range(9)]              # ten forks: more than one group can hold
-    for i, sq in enumerate(many):
-        for _ in range(3 * i):
-            mgr.append(sq)
-    seqs += many
-    mgr.take_copies()
+    # whose members share different numbers of blocks, a loner in between, a group of 5, a pair
+    # with exactly one full block in common, ten forks, forty forks (three groups)
     for dtype in ("f16", "bf16"):
-        filled = np.zeros((NB, B), dtype=bool)
-        for sq in seqs:
-            for j, pb in enumerate(sq.blocks):
-                filled[pb, : min(B, sq.length - j * B)] = True
-        mb = max(len(sq.blocks) for sq in seqs) + 1
-        bt = np.full((len(seqs), mb), -1, dtype=np.int32)
-        for i, sq in enumerate(seqs):
-            bt[i, : len(sq.blocks)] = sq.blocks
-        w = W.Workload("mixed", dtype, H, D, B, NB, np.float32(1 / np.sqrt(D)), bt,
-                       np.array([sq.length for sq in seqs], dtype=np.int32), filled,
-                       np.zeros((0, 2), dtype=np.int64), np.zeros(0, dtype=np.int64),
-                       np.zeros(len(seqs), dtype=np.int64), seed=34)
-        print(dtype, run_and_compare(pa, w, partitions=(SHARED, 0)))
+        print(dtype, run_and_compare(pa, mixed_sharing_workload(dtype), partitions=(SHARED, 0)))
+
+
+def test_shared_decode_group_of_forty_and_batch_wide_prefix(pa):
+    # one prompt forked 40 times (16 + 16 + 8), and one prefix mapped by every sequence of the batch
+    w = W.config3(seed=3021, num_groups=1, group=40, H=3, prompt_median=200, prompt_sigma=1e-9, prompt_cap=200, max_out=70)
+    assert w.num_seqs == 40
+    print(run_and_compare(pa, w, partitions=(SHARED, 0)))
+    for dtype_seed in (3022, 3023):
+        w = W.config3(seed=dtype_seed, num_groups=1, group=96, H=2, prompt_median=341, prompt_sigma=1e-9, prompt_cap=341,
+                      max_out=128)
+        print(run_and_compare(pa, w, partitions=(SHARED,)))
+    w = W.config5(seed=5031, num_seqs=36, width=12, H=2, min_len=200, max_len=700)     # beams of twelve, bf16, B = 32
+    print(run_and_compare(pa, w, partitions=(SHARED, 0)))
 
 
 def test_shared_plan_reused_across_layers(pa):
