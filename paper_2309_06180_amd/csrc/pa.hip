@@ -121,6 +121,10 @@ void launch_shared(const DecodeArgs &a)
         if (!(a.steps & SHARED_DECODE)) return;
         // groups + singles <= S: one workgroup per (sequence, head) always suffices
         const dim3 grid(S * (unsigned)a.p.H);
+#ifdef PA_EXP_SW
+        hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, PA_EXP_SW>), grid, dim3(PA_EXP_SW * kWave), 0, a.stream, a.p);
+        return;
+#endif
         if (a.waves >= 16)
             hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 16>), grid, dim3(16 * kWave), 0, a.stream, a.p);
         else if (a.waves >= 8)

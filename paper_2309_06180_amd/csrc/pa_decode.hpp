@@ -44,8 +44,9 @@ struct DecodeParams {
     float scale_log2;
 };
 
-// Sharing plan of pa_decode_shared.  The group table is 6 arrays of S int32 entries followed by
-// two counters:
+// Sharing plan of pa_decode_shared.  The group table is 6 arrays of S int32 entries, two
+// counters, and, from the next multiple of four words at or after word 6S + 4, S work items of
+// four int32 each:
 //   in_group[s]      1 if sequence s belongs to a group (two or more members), else 0
 //   group_size[s]    members of the group whose first sequence is s (consecutive sequences
 //                    s .. s + size - 1); 0 if no group starts at s
@@ -55,6 +56,11 @@ struct DecodeParams {
 //   single_list[i]   the sequences outside any group, ascending, i < single_count
 //   group_list[i]    first sequences of the groups, ascending, i < group_count
 //   group_count, single_count
+//   item[i]          what workgroup (i, head) of the decode launch does: (kind, first sequence,
+//                    members, tile-list entries) with kind 2 = group (i < group_count, order of
+//                    group_list), 1 = single sequence (the next single_count items, order of
+//                    single_list), 0 = nothing (the rest: every group takes the place of two or
+//                    more sequences)
 // The tile list of the group that starts at s begins at entry s * max_blocks of the tile array
 // (a group's members own that many entries between them).  It holds every physical block
 // that a member maps, once per logical position, ordered by position:
@@ -72,7 +78,9 @@ __device__ __host__ __forceinline__ int ginfo_single_list(int S, int i) { return
 __device__ __host__ __forceinline__ int ginfo_group_list(int S, int i) { return 5 * S + i; }
 __device__ __host__ __forceinline__ int ginfo_group_count(int S) { return 6 * S; }
 __device__ __host__ __forceinline__ int ginfo_single_count(int S) { return 6 * S + 1; }
-__device__ __host__ __forceinline__ size_t ginfo_words(int S) { return 6 * (size_t)S + 4; }
+// (items are 16-byte records: they start at the next multiple of four words)
+__device__ __host__ __forceinline__ int ginfo_item(int S, int i) { return (6 * S + 4 + 3) / 4 * 4 + 4 * i; }
+__device__ __host__ __forceinline__ size_t ginfo_words(int S) { return (size_t)ginfo_item(S, 0) + 4 * (size_t)S; }
 
 // A sixteen-wave workgroup is kept alone on its compute unit (at most 7 waves
 // per SIMD, so a second one does not fit): measured on batches of mixed

@@ -235,7 +235,10 @@ __global__ __launch_bounds__(kPlanThreads) void shared_plan_kernel(
             if (flag) {
                 const int at = before + __builtin_popcountll(mask & ((1ull << lane) - 1));
                 if (which == 0) s_list[at] = (uint16_t)sq;
-                if (writer) ginfo[which == 0 ? ginfo_group_list(S, at) : ginfo_single_list(S, at)] = sq;
+                if (which == 1 && writer) {
+                    ginfo[ginfo_single_list(S, at)] = sq;
+                    *reinterpret_cast<int4 *>(ginfo + ginfo_item(S, n_groups + at)) = make_int4(1, sq, 1, 0);
+                }
             }
             __syncthreads();
             if (threadIdx.x == 0) {
@@ -252,12 +255,27 @@ __global__ __launch_bounds__(kPlanThreads) void shared_plan_kernel(
         __syncthreads();
     }
 
+    int32_t *const items = ginfo + ginfo_item(S, 0);
+    if (writer) {
+        const int n_single = running;      // left by the second compaction
+        for (int i = threadIdx.x; i < S; i += kPlanThreads) {
+            if (i < n_groups)
+                ginfo[ginfo_group_list(S, i)] = s_list[i];
+            else if (i >= n_groups + n_single)
+                *reinterpret_cast<int4 *>(items + 4 * i) = make_int4(0, 0, 0, 0);
+        }
+    }
+
     // tile lists: the wavefronts of all workgroups take the groups in turn
     for (int gi = blockIdx.x * NW + w; gi < n_groups; gi += gridDim.x * NW) {
         const int start = s_list[gi];
-        const int placed = build_tile_list(block_tables, max_blocks, block_size, start, s_size[start],
+        const int G = s_size[start];
+        const int placed = build_tile_list(block_tables, max_blocks, block_size, start, G,
                                            tiles + (int64_t)start * max_blocks, s_len + start);
-        if (lane == 0) ginfo[ginfo_tile_count(S, start)] = placed;
+        if (lane == 0) {
+            ginfo[ginfo_tile_count(S, start)] = placed;
+            *reinterpret_cast<int4 *>(items + 4 * gi) = make_int4(2, start, G, placed);
+        }
     }
 }
 

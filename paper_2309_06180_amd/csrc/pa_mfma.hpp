@@ -81,16 +81,16 @@ __device__ __forceinline__ uint4 weight_operand(const float (&p)[4])
         o.z = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a0 - (float)h01.x, a1 - (float)h01.y));
         o.w = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a2 - (float)h23.x, a3 - (float)h23.y));
     } else {
-        uint32_t hi[4], lo[4];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            hi[v] = Traits<PA_BF16>::rne(p[v]);
-            lo[v] = Traits<PA_BF16>::rne(p[v] - as_f32(hi[v] << 16));
-        }
-        o.x = hi[0] | (hi[1] << 16);
-        o.y = hi[2] | (hi[3] << 16);
-        o.z = lo[0] | (lo[1] << 16);
-        o.w = lo[2] | (lo[3] << 16);
+        // v_cvt_pk_bf16_f32 rounds to nearest even
+        typedef float float2v __attribute__((ext_vector_type(2)));
+        const uint32_t h01 = __builtin_bit_cast(uint32_t, __builtin_convertvector(float2v{p[0], p[1]}, bf16x2v_t));
+        const uint32_t h23 = __builtin_bit_cast(uint32_t, __builtin_convertvector(float2v{p[2], p[3]}, bf16x2v_t));
+        const float2v r01 = {p[0] - as_f32(h01 << 16), p[1] - as_f32(h01 & 0xffff0000u)};
+        const float2v r23 = {p[2] - as_f32(h23 << 16), p[3] - as_f32(h23 & 0xffff0000u)};
+        o.x = h01;
+        o.y = h23;
+        o.z = __builtin_bit_cast(uint32_t, __builtin_convertvector(r01, bf16x2v_t));
+        o.w = __builtin_bit_cast(uint32_t, __builtin_convertvector(r23, bf16x2v_t));
     }
     return o;
 }
@@ -467,7 +467,8 @@ __global__ __launch_bounds__(4 * kWave) __attribute__((amdgpu_waves_per_eu(4, 8)
 // column outside a tile's set is masked like a token outside a query's context.  A shared
 // block is therefore read once for all its readers, an unshared one once for its owner.
 template <int DT, int B, int W>
-__device__ __forceinline__ void group_item(const DecodeParams &P, const int group, const int h)
+__device__ __forceinline__ void group_item(const DecodeParams &P, const int s0, int members, const int entries,
+                                           const int h)
 {
     constexpr int ROW_BYTES = 256, SUBS = B / kTileTokens;
     constexpr int64_t TILE_BYTES = (int64_t)B * ROW_BYTES;
@@ -479,10 +480,8 @@ __device__ __forceinline__ void group_item(const DecodeParams &P, const int grou
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int c = lane % 16;
     const int H = P.H;
-    const int s0 = P.ginfo[ginfo_group_list(P.S, group)];      // a group is named by its first sequence
-    int members = P.ginfo[ginfo_group_size(P.S, s0)];
     members = members > kGroupMax ? kGroupMax : members;
-    const int nwork = P.ginfo[ginfo_tile_count(P.S, s0)] * SUBS;   // 16-token tiles on the list
+    const int nwork = entries * SUBS;                          // 16-token tiles on the list
     const uint32_t everyone = (1u << members) - 1u;
 
     QueryCols Q;
@@ -518,22 +517,22 @@ __device__ __forceinline__ void group_item(const DecodeParams &P, const int grou
     split_merge_store<DT, W>(Q, sm_region, sm_m, sm_l, members, P.out, (int64_t)s0, 1, H, h);
 }
 
-// pa_decode_shared's main launch, grid = S x H workgroups: the first group_count x H are
-// (group, head) items, the next single_count x H are (sequence, head) items of the ordinary
-// one-pass kernel for the sequences outside any group, and what is left of the grid (every
-// group takes the place of two or more sequences) ends at once.
+// pa_decode_shared's main launch, grid = S x H workgroups, the plan's work item i for workgroups
+// (i, head): first the (group, head) items, longest first, then the (sequence, head) items of
+// the ordinary one-pass kernel for the sequences outside any group; what is left of the grid
+// (every group takes the place of two or more sequences) ends at once.
 template <int DT, int B, int W>
 __global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) void pa_shared_fused_kernel(
     const DecodeParams P)
 {
     const int h = (int)blockIdx.x % P.H;
     const int item = (int)blockIdx.x / P.H;
-    const int groups = P.ginfo[ginfo_group_count(P.S)];
-    if (item < groups) {
-        group_item<DT, B, W>(P, item, h);
-    } else if (item - groups < P.ginfo[ginfo_single_count(P.S)]) {
-        decode_body<DT, 128, B, W, kChunksPerTrip, MODE_SINGLE>(P, P.ginfo[ginfo_single_list(P.S, item - groups)], h, 0);
-    }
+    // (kind, first sequence, members, tile-list entries): one scalar load says what to do
+    const int4 d = *reinterpret_cast<const int4 *>(P.ginfo + ginfo_item(P.S, item));
+    if (d.x == 2)
+        group_item<DT, B, W>(P, d.y, d.z, d.w, h);
+    else if (d.x == 1)
+        decode_body<DT, 128, B, W, kChunksPerTrip, MODE_SINGLE>(P, d.y, h, 0);
 }
 
 } // namespace

@@ -13,7 +13,8 @@ physical blocks):
   * a maximal chain of tied sequences is cut into groups of at most 16, in order; groups of
     one are "singles";
   * a group's tile list holds, position by position, each distinct physical block that some
-    member maps at that position, with the set of members mapping it there.
+    member maps at that position, with the set of members mapping it there;
+  * work item i is group i (ascending), then the singles ascending, then nothing.
 """
 from __future__ import annotations
 
@@ -84,16 +85,30 @@ def plan(block_tables: np.ndarray, context_lens: np.ndarray, B: int, tie_rule=No
     return dict(adj=adj, in_group=in_group, group_size=group_size, groups=groups, singles=singles, tiles=tiles)
 
 
+def items_of(p, S):
+    """The S work items (kind, first, members, entries) that a plan implies."""
+    items = [(2, first, size, len(p["tiles"][first])) for first, size in p["groups"]]
+    items += [(1, s, 1, 0) for s in p["singles"]]
+    items += [(0, 0, 0, 0)] * (S - len(items))
+    return items
+
+
+def plan_words(S: int) -> int:
+    return (6 * S + 4 + 3) // 4 * 4 + 4 * S
+
+
 def decode_device_plan(raw: np.ndarray, S: int, max_blocks: int):
     """Splits the bytes of a device plan (the workspace pa_shared_plan filled) by the documented layout."""
     words = raw.view(np.int32)
-    g = words[: 6 * S + 4]
-    ginfo_bytes = ((6 * S + 4) * 4 + 15) // 16 * 16
+    g = words[: plan_words(S)]
+    ginfo_bytes = (plan_words(S) * 4 + 15) // 16 * 16
     tiles = raw[ginfo_bytes: ginfo_bytes + S * max_blocks * 16].view(np.int32).reshape(S * max_blocks, 4)
     group_count, single_count = int(g[6 * S]), int(g[6 * S + 1])
+    item0 = (6 * S + 4 + 3) // 4 * 4
     out = dict(in_group=g[0:S].tolist(), group_size=g[S:2 * S].tolist(), tile_count=g[2 * S:3 * S].tolist(),
                adj=g[3 * S:4 * S].tolist(), singles=g[4 * S:4 * S + single_count].tolist(),
-               group_firsts=g[5 * S:5 * S + group_count].tolist(), tiles={})
+               group_firsts=g[5 * S:5 * S + group_count].tolist(),
+               items=[tuple(int(x) for x in g[item0 + 4 * i: item0 + 4 * i + 4]) for i in range(S)], tiles={})
     for first in out["group_firsts"]:
         cnt = out["tile_count"][first]
         ent = tiles[first * max_blocks: first * max_blocks + cnt]

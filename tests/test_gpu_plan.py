@@ -49,6 +49,7 @@ def check(pa, w, min_groups=1, expect_sizes=None):
     assert got["group_size"] == want["group_size"]
     assert got["group_firsts"] == [f for f, _ in want["groups"]]
     assert got["singles"] == want["singles"]
+    assert got["items"] == ref.items_of(want, w.num_seqs)
     assert len(got["group_firsts"]) >= min_groups, "no sharing found: the decode would run the one-pass path only"
     for first, size in want["groups"]:
         assert got["tiles"][first] == want["tiles"][first], "tile list of the group at %d differs" % first
@@ -85,7 +86,8 @@ def test_plan_mixed_patterns(pa):
     # pair with a single 16-token block in common (too little to be worth a group) stay on their own
     assert sizes == sorted([3, 5, 10, 16, 16, 8]), sizes
     assert want["singles"] == [3, 9, 10]
-    first = want["groups"][0][0]
+    first = 0
+    assert (0, 3) in want["groups"]
     # un-diverged forks: every block, the partial last one included, is listed once for all three
     assert all(e[1] == 0b111 for e in want["tiles"][first]) and len(want["tiles"][first]) == 5
     assert want["tiles"][first][-1][2] == 1 and want["tiles"][first][-1][4] == 70 - 64
@@ -104,3 +106,4 @@ def test_plan_without_sharing_is_empty(pa):
     w = W.independent_sequences("private", "f16", 2, 128, 16, lens, seed=32)
     got = device_plan(pa, w)
     assert got["group_firsts"] == [] and got["singles"] == list(range(40)) and not any(got["in_group"])
+    assert got["items"] == [(1, s, 1, 0) for s in range(40)]

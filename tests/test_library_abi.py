@@ -100,8 +100,9 @@ def test_argument_errors_of_the_wider_entry_points(lib):
                                             a["ws"], a["wsb"], None)
 
     need = lib.pa_decode_shared_workspace_bytes(2, 2, 128, 8)
-    assert need == ((6 * 2 + 4) * 4 + 15) // 16 * 16 + 2 * 8 * 16   # group table + one 16-byte tile entry per table entry
-    assert lib.pa_decode_shared_workspace_bytes(5, 2, 128, 3) == ((6 * 5 + 4) * 4 + 15) // 16 * 16 + 5 * 3 * 16
+    # group table (6S + 2 words, rounded up to four, + S items of four words) + one 16-byte tile entry per table entry
+    assert need == (16 + 4 * 2) * 4 + 2 * 8 * 16
+    assert lib.pa_decode_shared_workspace_bytes(5, 2, 128, 3) == (36 + 4 * 5) * 4 + 5 * 3 * 16
     for fn in (lib.pa_decode_shared, lib.pa_decode_shared_planned):
         assert shared(fn, S=0) == 0
         assert shared(fn, k=None) == 1

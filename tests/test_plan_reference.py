@@ -55,15 +55,26 @@ def test_subsets_sharing_beyond_the_common_prefix():
                              (20, 0b001, 0, 3, 16), (21, 0b010, 0, 3, 16), (22, 0b100, 1, 3, 8)]
 
 
+def test_work_items_are_groups_then_singles_then_nothing():
+    rows = [[1, 2, 10], [1, 2, 11], [9], [3, 4, 5, 6, 12], [3, 4, 5, 6, 13], [7, 8, 14]]
+    p = ref.plan(tables(rows, 5), np.array([40, 40, 9, 70, 70, 40], dtype=np.int32), 16)
+    assert p["groups"] == [(0, 2), (3, 2)] and p["singles"] == [2, 5]
+    assert ref.items_of(p, 6) == [(2, 0, 2, 4), (2, 3, 2, 6), (1, 2, 1, 0), (1, 5, 1, 0), (0, 0, 0, 0), (0, 0, 0, 0)]
+
+
 def test_decode_device_plan_layout():
     S, MB = 3, 2
-    words = np.zeros(6 * S + 4, dtype=np.int32)
+    nwords = ref.plan_words(S)
+    assert nwords == 24 + 12                      # 6S + 4 = 22 -> items start at word 24
+    words = np.zeros(nwords, dtype=np.int32)
     words[0:3] = [1, 1, 0]; words[3:6] = [2, 0, 1]; words[6:9] = [1, 0, 0]; words[9:12] = [0, 2, 0]
     words[12] = 2; words[15] = 0; words[18] = 1; words[19] = 1
-    raw = np.zeros(((6 * S + 4) * 4 + 15) // 16 * 16 + S * MB * 16, dtype=np.uint8)
+    words[24:28] = [2, 0, 2, 1]; words[28:32] = [1, 2, 1, 0]
+    off = (nwords * 4 + 15) // 16 * 16
+    raw = np.zeros(off + S * MB * 16, dtype=np.uint8)
     raw[: words.nbytes] = words.view(np.uint8)
     ent = np.array([5, 0b11 | (1 << 16), 0, 9], dtype=np.int32)
-    off = ((6 * S + 4) * 4 + 15) // 16 * 16
     raw[off: off + 16] = ent.view(np.uint8)
     got = ref.decode_device_plan(raw, S, MB)
     assert got["group_firsts"] == [0] and got["singles"] == [2] and got["tiles"][0] == [(5, 0b11, 1, 0, 9)]
+    assert got["items"] == [(2, 0, 2, 1), (1, 2, 1, 0), (0, 0, 0, 0)]
