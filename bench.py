@@ -50,6 +50,10 @@ def parse():
                     help="also run one pa_copy_blocks of known size (a plain copy kernel that "
                          "hardware-counter runs use to scale FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--others", dest="others", action="store_true", default=None,
+                    help="also time configs 3, 4 and 5 (one layer) each way and add them to the line as \"others\" "
+                         "(default for the default workload)")
+    ap.add_argument("--no-others", dest="others", action="store_false")
     ap.add_argument("--block-size-sweep", action="store_true",
                     help="instead of the step benchmark: pa_decode at the OPT-13B shape for B = 8..128")
     ap.add_argument("--cfg5-full-step", action="store_true",
@@ -74,9 +78,21 @@ def parse():
     return ap.parse_args()
 
 
+def source_hash():
+    """Hash of the library's sources: ties a figure measured elsewhere (a counter pass) to the code it was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2309_06180_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def profiled_traffic(workload_name):
-    """HBM bytes per pa_decode launch from the committed hardware-counter summary (FETCH_SIZE and
-    WRITE_SIZE passes of rocprofv3, scaled by a plain copy of known size), or None."""
+    """(HBM bytes per pa_decode launch, source) from the committed hardware-counter summary (FETCH_SIZE and
+    WRITE_SIZE passes of rocprofv3, scaled by a plain copy of known size).  The summary names the hash of
+    pa_decode's kernel file it was measured on: if that file has changed since, the figure is withheld."""
+    import hashlib
     path = os.path.join(ROOT, "profiles", "pa_decode_opt13b_hbm_traffic.md")
     try:
         kv = {}
@@ -84,24 +100,42 @@ def profiled_traffic(workload_name):
             if ":" in line and not line.startswith(("#", "|", " ")):
                 k, _, val = line.partition(":")
                 kv[k.strip()] = val.strip()
-        if kv.get("workload") == workload_name:
-            return int(kv["traffic_bytes_per_launch"])
+        kernel_file = os.path.join(ROOT, "paper_2309_06180_amd", "csrc", "pa_decode.hpp")
+        now = hashlib.sha256(open(kernel_file, "rb").read()).hexdigest()[:16]
+        if kv.get("workload") != workload_name:
+            return None, "no counter summary for this workload"
+        if kv.get("pa_decode_hpp_sha16") != now:
+            return None, "profiles/pa_decode_opt13b_hbm_traffic.md was measured on another version of pa_decode.hpp"
+        return int(kv["traffic_bytes_per_launch"]), ("profiles/pa_decode_opt13b_hbm_traffic.md (two rocprofv3 --pmc passes, "
+                                                       "pa_decode.hpp sha16 %s; not measured by this run)" % now)
     except (OSError, KeyError, ValueError):
-        pass
-    return None
+        return None, "no counter summary"
+
+
+def _time_calls_us(fn, iters, torch, warmup=3):
+    """Per-call GPU time of `fn` in us: an event pair around every call, on torch's current stream, which
+    is the stream the library launches on.  Returns the list of the `iters` durations."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
+    for i in range(iters):
+        starts[i].record()
+        fn()
+        ends[i].record()
+    torch.cuda.synchronize()
+    return [starts[i].elapsed_time(ends[i]) * 1e3 for i in range(iters)]
+
+
+def _stats(us):
+    srt = sorted(us)
+    return {"mean_us": sum(us) / len(us), "median_us": srt[len(srt) // 2], "min_us": srt[0]}
 
 
 def _time_us(fn, iters, torch):
-    for _ in range(3):
-        fn()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(iters):
-        fn()
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / iters * 1e3
+    """Median per-call time in us."""
+    return _stats(_time_calls_us(fn, iters, torch))["median_us"]
 
 
 def block_size_sweep(pa, W, np, torch, dev):
@@ -357,6 +391,72 @@ def cache_ops(pa, np, torch, dev):
     print(json.dumps(res))
 
 
+def _to_host_storage(t, dtype, np, torch):
+    t = t.cpu()
+    if dtype == "bf16":
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
+
+
+def others(pa, W, np, torch, dev, iters=30):
+    """The other configurations of the benchmark spec, one decode launch each way, so that one run of the benchmark
+    backs their figures too: config 3 (parallel sampling) and config 5 (beam search, one of its 40 layers)
+    through pa_decode, pa_decode_shared (sharing plan built per call) and pa_decode_shared_planned (plan
+    built once, as once per decoding step for all layers); config 4 in one pass and split at 512 tokens.
+    Caches are filled on the device with seeded N(0,1) values (every slot, so the unused ones hold finite
+    junk here; NaN in unused slots is what the tests cover).  Per entry: median / min / mean us over `iters`
+    launches, algorithmic bytes (distinct K/V bytes once + q in + out), the fraction of the 8 TB/s HBM peak
+    on those bytes, and the max abs error against the fp64 oracle on 32 sampled (sequence, head) rows."""
+    import oracle
+    from harness.workloads import storage_to_f64
+    out = {}
+    tdt = {"f16": torch.float16, "bf16": torch.bfloat16}
+    for name, w, ways in (("cfg3_parallel_sampling", W.config3(), ("plain", "shared", "shared_planned")),
+                          ("cfg4_opt66b_tp4", W.config4(), ("one_pass", "split_512")),
+                          ("cfg5_beam_search_one_layer", W.config5(), ("plain", "shared", "shared_planned"))):
+        S, H, D, B, NB = w.num_seqs, w.num_heads, w.head_dim, w.block_size, w.num_blocks
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(w.seed + 9)
+        kc = torch.randn((NB, H, B, D), device=dev, dtype=tdt[w.dtype], generator=gen)
+        vc = torch.randn((NB, H, B, D), device=dev, dtype=tdt[w.dtype], generator=gen)
+        q = torch.randn((S, H, D), device=dev, dtype=tdt[w.dtype], generator=gen)
+        bt, cl = torch.from_numpy(w.block_tables).to(dev), torch.from_numpy(w.context_lens).to(dev)
+        mcl = w.max_context_len
+        ws = torch.empty(max(pa.pa_decode_shared_workspace_bytes(S, H, D, w.max_blocks_per_seq),
+                             pa.pa_decode_workspace_bytes(S, H, D, B, mcl, 512), 16), dtype=torch.uint8, device=dev)
+        rng = np.random.default_rng(w.seed + 1)
+        rows = np.stack([rng.integers(0, S, size=32), rng.integers(0, H, size=32)], axis=1).astype(np.int32)
+        hk, hv = _to_host_storage(kc, w.dtype, np, torch), _to_host_storage(vc, w.dtype, np, torch)
+        ref = oracle.decode(_to_host_storage(q, w.dtype, np, torch), hk, hv, w.block_tables, w.context_lens, w.scale,
+                            w.dtype, rows=rows)
+        del hk, hv
+        unique = w.kv_bytes_unique()
+        algo = unique + 2 * S * H * D * w.elem_bytes
+        entry = {"num_seqs": S, "context_tokens": int(w.context_lens.sum()), "kv_bytes_logical": w.kv_bytes_logical(),
+                 "kv_bytes_unique": unique, "algorithmic_bytes": algo, "dtype": w.dtype, "calls": {}}
+        for way in ways:
+            o = torch.full_like(q, float("nan"))
+            if way in ("plain", "one_pass"):
+                fn = lambda: pa.pa_decode(o, q, kc, vc, bt, cl, B, float(w.scale), mcl, 0, None)
+            elif way == "split_512":
+                fn = lambda: pa.pa_decode(o, q, kc, vc, bt, cl, B, float(w.scale), mcl, 512, ws)
+            elif way == "shared":
+                fn = lambda: pa.pa_decode_shared(o, q, kc, vc, bt, cl, B, float(w.scale), mcl, ws)
+            else:
+                pa.pa_shared_plan(bt, cl, H, D, B, NB, tdt[w.dtype], mcl, ws)
+                fn = lambda: pa.pa_decode_shared_planned(o, q, kc, vc, bt, cl, B, float(w.scale), mcl, ws)
+            st = _stats(_time_calls_us(fn, iters, torch))
+            torch.cuda.synchronize()
+            got = storage_to_f64(_to_host_storage(o, w.dtype, np, torch), w.dtype)[rows[:, 0], rows[:, 1]]
+            st["frac_of_hbm_peak"] = algo / st["median_us"] / 1e3 / HBM_PEAK_GBPS
+            st["max_abs_err_sampled"] = float(np.abs(got - ref).max())
+            entry["calls"][way] = st
+        out[name] = entry
+        del kc, vc
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -392,6 +492,8 @@ def main():
     if args.cfg5_full_step:
         return cfg5_full_step(pa, W, np, torch, dev, min(args.steps, 10))
 
+    if args.others is None:
+        args.others = args.workload == "cfg2" and args.decode == "plain" and args.partition is None
     make = {"cfg1": W.config1, "cfg2": W.config2, "cfg3": W.config3, "cfg4": W.config4,
             "cfg5": W.config5}[args.workload]
     w = make()
@@ -503,7 +605,12 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
 
-    # dominant kernel alone: events on the launch stream around back-to-back decodes
+    # the same steps once more with an event pair around each: median and minimum next to the mean
+    step_stats = _stats(_time_calls_us(run_step, args.steps, torch, warmup=2))
+
+    # dominant kernel alone: one event pair on the launch stream around `steps` back-to-back decodes (the
+    # mean that the roofline uses; it agrees with the profiler's kernel durations), then an event pair
+    # around every call for the median and the minimum (each of those includes the pair's own ~2 us)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for _ in range(5):
         decode()
@@ -514,6 +621,7 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     decode_ms = e0.elapsed_time(e1) / args.steps
+    decode_stats = _stats(_time_calls_us(decode, args.steps, torch, warmup=2))
 
     # streaming-read ceiling of this device, for context
     probe = torch.empty(2 * 1024 ** 3, dtype=torch.uint8, device=dev)
@@ -530,6 +638,8 @@ def main():
     stream_gbps = probe.numel() / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e9
     del probe
 
+    traffic, traffic_source = (profiled_traffic(w.name) if ps in (0, pa.PA_PARTITION_AUTO) and not shared
+                               else (None, "no counter summary for this call"))
     result = {
         "metric": "pa_decode_kv_read_GBps",
         "value": kv_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -545,14 +655,17 @@ def main():
                    "step": "copy_blocks(0 pairs)+reshape_and_cache(T=S)+pa_decode"},
         "query_tokens_per_s": S / (ms_per_step * 1e-3),
         "pct_of_hbm_peak": 100.0 * kv_unique / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "step_us_per_call_events": step_stats,
         "decode_only_ms": decode_ms,
+        "decode_only_us_per_call_events": decode_stats,
         "stream_read_GBps": stream_gbps,
         "roofline": {"bound": "hbm", "achieved": algo_bytes / (decode_ms * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": algo_bytes / (decode_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                     "traffic": profiled_traffic(w.name) if ps in (0, pa.PA_PARTITION_AUTO) and not shared else None,
-                     "kernel": "pa_decode_kernel",
+                     "traffic": traffic, "traffic_source": traffic_source,
+                     "kernel": "pa_shared_fused_kernel" if shared else "pa_decode_kernel",
                      "algorithmic_bytes_per_launch": algo_bytes},
+        "library_source_sha16": source_hash(),
     }
 
     if calib:
@@ -587,12 +700,28 @@ def main():
                                         threads=0, return_threads=True)
                 passes += 1
             cdt = (time.perf_counter() - t0) / passes
+            # one thread: every 16th (sequence, head) row of the same batch, scaled to the whole
+            all_rows = np.stack(np.meshgrid(np.arange(S), np.arange(H), indexing="ij"), axis=-1).reshape(-1, 2)
+            sub = np.ascontiguousarray(all_rows[::16]).astype(np.int32)
+            t0 = time.perf_counter()
+            oracle.decode(v.q, hk, hv, w.block_tables, w.context_lens, w.scale, w.dtype, rows=sub, threads=1)
+            one = time.perf_counter() - t0
+            sub_bytes = int(w.context_lens[sub[:, 0]].astype(np.int64).sum()) * D * w.elem_bytes * 2
             result["cpu_baseline"] = {"value": kv_bytes / cdt / 1e9, "unit": "GB/s", "cores": int(used),
                                       "kind": "oracle",
                                       "sample": "%d full pa_decode passes over the same batch (%d sequences x %d "
                                                 "heads, %d cached tokens), %.2f s each"
                                                 % (passes, S, H, int(w.context_lens.sum()), cdt),
-                                      "query_tokens_per_s": S / cdt}
+                                      "query_tokens_per_s": S / cdt,
+                                      "one_thread": {"value": sub_bytes / one / 1e9, "unit": "GB/s", "cores": 1,
+                                                     "sample": "every 16th (sequence, head) row of the same batch, "
+                                                               "%.2f s" % one}}
+    if args.others:
+        del d_kc, d_vc
+        if args.cache_allocation == "one":
+            del arena
+        torch.cuda.empty_cache()
+        result["others"] = others(pa, W, np, torch, dev)
     print(json.dumps(result))
 
 
