@@ -362,10 +362,19 @@ def cache_ops(pa, np, torch, dev):
     for T in (64, 256, 1024, 4096, 16384, 65536):
         k = torch.randn((T, H, D), dtype=torch.float16, device=dev)
         v = torch.randn((T, H, D), dtype=torch.float16, device=dev)
-        slots = torch.from_numpy(rng.permutation(NB * B)[:T].astype(np.int64)).to(dev)
-        us = _time_us(lambda: pa.pa_reshape_and_cache(k, v, kc, vc, slots), 50, torch)
         moved = 2 * 2 * T * H * D * 2
-        res["reshape_and_cache"].append({"tokens": T, "us": us, "GBps": moved / us / 1e3})
+        # "scattered": every token in a slot of its own block, as the new tokens of T decoding sequences are;
+        # "prompt": consecutive tokens fill consecutive slots of randomly placed blocks, as a prompt does (Sec. 4.3)
+        scattered = rng.permutation(NB * B)[:T].astype(np.int64)
+        blocks = rng.permutation(NB)[: (T + B - 1) // B].astype(np.int64)
+        prompt = (blocks[:, None] * B + np.arange(B)[None, :]).reshape(-1)[:T]
+        row = {"tokens": T}
+        for name, sl in (("scattered", scattered), ("prompt", prompt)):
+            slots = torch.from_numpy(np.ascontiguousarray(sl)).to(dev)
+            us = _time_us(lambda: pa.pa_reshape_and_cache(k, v, kc, vc, slots), 50, torch)
+            row[name + "_us"] = us
+            row[name + "_GBps"] = moved / us / 1e3
+        res["reshape_and_cache"].append(row)
     for N in (4, 41, 183, 1024, 4096):
         perm = rng.permutation(NB)
         pairs = torch.from_numpy(np.stack([perm[:N], perm[N:2 * N]], axis=1).astype(np.int64)).to(dev)

@@ -100,7 +100,10 @@ enum SharedSteps { SHARED_PLAN = 1, SHARED_DECODE = 2 };
 template <int DT, int D, int B, int W, int MODE>
 void launch_decode_kernel(const DecodeArgs &a, unsigned items)
 {
-    hipLaunchKernelGGL((pa_decode_kernel<DT, D, B, W, MODE == MODE_PART ? kPartChunksPerTrip : kChunksPerTrip, MODE>),
+#ifndef PA_EXP_U
+#define PA_EXP_U kChunksPerTrip
+#endif
+    hipLaunchKernelGGL((pa_decode_kernel<DT, D, B, W, MODE == MODE_PART ? kPartChunksPerTrip : PA_EXP_U, MODE>),
                        dim3(items * (unsigned)a.p.H),
                        dim3(W * kWave), 0, a.stream, a.p);
 }
@@ -121,10 +124,6 @@ void launch_shared(const DecodeArgs &a)
         if (!(a.steps & SHARED_DECODE)) return;
         // groups + singles <= S: one workgroup per (sequence, head) always suffices
         const dim3 grid(S * (unsigned)a.p.H);
-#ifdef PA_EXP_SW
-        hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, PA_EXP_SW>), grid, dim3(PA_EXP_SW * kWave), 0, a.stream, a.p);
-        return;
-#endif
         if (a.waves >= 16)
             hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 16>), grid, dim3(16 * kWave), 0, a.stream, a.p);
         else if (a.waves >= 8)
@@ -144,11 +143,14 @@ void dispatch_mode(const DecodeArgs &a, int mode)
             launch_decode_kernel<DT, D, B, 8, MODE_PART>(a, S * (unsigned)a.p.max_parts);
         else
             launch_decode_kernel<DT, D, B, 4, MODE_PART>(a, S * (unsigned)a.p.max_parts);
-        hipLaunchKernelGGL((pa_reduce_kernel<DT, D>), dim3(rows), dim3(kWave), 0, a.stream, a.p);
+        constexpr unsigned kRowsPerGroup = kReduceWaves * kWave / (D * (DT == PA_F32 ? 4 : 2) / 16);
+        hipLaunchKernelGGL((pa_reduce_kernel<DT, D>), dim3((rows + kRowsPerGroup - 1) / kRowsPerGroup),
+                           dim3(kReduceWaves * kWave), 0, a.stream, a.p);
     } else if (mode == PLAN_SHARED) {
         launch_shared<DT, D, B>(a);
     } else {
         switch (a.waves) {
+        case 1: launch_decode_kernel<DT, D, B, 1, MODE_SINGLE>(a, S); break;
         case 2: launch_decode_kernel<DT, D, B, 2, MODE_SINGLE>(a, S); break;
         case 4: launch_decode_kernel<DT, D, B, 4, MODE_SINGLE>(a, S); break;
         case 8: launch_decode_kernel<DT, D, B, 8, MODE_SINGLE>(a, S); break;
@@ -213,6 +215,9 @@ int chunk_tokens(pa_dtype dt, int D, int B)
 int waves_for(int tokens_per_item, int ct)
 {
     const int chunks = (tokens_per_item + ct - 1) / ct;
+#ifdef PA_EXP_SHORTW
+    if (chunks <= 16) return PA_EXP_SHORTW;
+#endif
     if (chunks <= 4) return 2;
     if (chunks <= 16) return 4;
     if (chunks <= 32) return 8;

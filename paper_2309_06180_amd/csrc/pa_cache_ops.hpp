@@ -9,6 +9,10 @@ namespace {
 // ---- reshape_and_cache -------------------------------------------------------
 // One thread moves one 16-byte fragment.  A token is frags_per_token = H*D*E/16
 // fragments; fragment r of token t belongs to head r / frags_per_row.
+// (Measured and not adopted: one workgroup per token with the slot looked up once, no
+// divisions, and up to four fragments per thread issued before the first store - 5.26
+// instead of 5.48 TB/s of read+write traffic at 65 536 tokens.  As with the block copy,
+// many small workgroups of one fragment per thread are what this memory system likes.)
 __global__ __launch_bounds__(256) void reshape_and_cache_kernel(
     const uint4 *__restrict__ k, const uint4 *__restrict__ v, uint4 *__restrict__ k_cache,
     uint4 *__restrict__ v_cache, const int64_t *__restrict__ slot_mapping, int64_t total_frags,
@@ -40,9 +44,10 @@ struct CachePtrs {
 };
 
 // grid = (256-fragment slices of a block, pairs, caches); a block of one cache
-// is frags_per_block consecutive 16-byte fragments.  One fragment per thread:
-// with randomly placed pairs, many small workgroups measured 5.9 TB/s of
-// read+write traffic against 5.2 TB/s with four fragments per thread.
+// is frags_per_block consecutive 16-byte fragments.  One fragment per thread in
+// workgroups of 256: with 4096 randomly placed pairs that measured 5.86 TB/s of
+// read+write traffic, against 5.25 with two fragments per thread, 5.53 / 5.07 with
+// workgroups of 512 / 1024 threads and 5.06 with 512 threads x two fragments.
 __global__ __launch_bounds__(256) void copy_blocks_kernel(CachePtrs caches,
                                                            const int64_t *__restrict__ pairs,
                                                            int64_t frags_per_block)

@@ -131,15 +131,25 @@ __device__ __forceinline__ void stream_range(const DecodeParams &P, const int s,
         // ci is wave-uniform: this is a scalar load
         return table[(t_begin + ci * CT) / B];
     };
-    auto issue = [&](Chunk &ck, int ci, int pb) {
+    // TAIL is set only for a chunk that may reach past t_end (the last one): rows that hold no
+    // token of the range are not fetched at all (with contexts of a few dozen tokens they would
+    // be a tenth of the traffic) and read as zeros
+    auto issue = [&](Chunk &ck, int ci, int pb, auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
         const int t0 = t_begin + ci * CT;
         const int64_t off = ((int64_t)pb * H + h) * TILE_BYTES + (int64_t)(t0 % B) * ROW_BYTES;
         const char *kp = P.k_cache + off + lane16;
         const char *vp = P.v_cache + off + lane16;
 #pragma unroll
-        for (int i = 0; i < LPC; ++i) ck.k[i] = load16_stream(kp + i * 1024);
+        for (int i = 0; i < LPC; ++i) {
+            ck.k[i] = make_uint4(0, 0, 0, 0);
+            if (!TAIL || t0 + i * TPL + g < t_end) ck.k[i] = load16_stream(kp + i * 1024);
+        }
 #pragma unroll
-        for (int i = 0; i < LPC; ++i) ck.v[i] = load16_stream(vp + i * 1024);
+        for (int i = 0; i < LPC; ++i) {
+            ck.v[i] = make_uint4(0, 0, 0, 0);
+            if (!TAIL || t0 + i * TPL + g < t_end) ck.v[i] = load16_stream(vp + i * 1024);
+        }
     };
     // MASK is set only for a chunk that may reach past t_end (the last one)
     auto consume = [&](Chunk &ck, int ci, auto mask_tag) {
@@ -200,13 +210,13 @@ __device__ __forceinline__ void stream_range(const DecodeParams &P, const int s,
 #pragma unroll
             for (int u = 0; u < U; ++u) pb[u] = block_of(ci + u * nw);
 #pragma unroll
-            for (int u = 0; u < U; ++u) issue(ck[u], ci + u * nw, pb[u]);
+            for (int u = 0; u < U; ++u) issue(ck[u], ci + u * nw, pb[u], full);
 #pragma unroll
             for (int u = 0; u < U; ++u) consume(ck[u], ci + u * nw, full);
         }
         for (; ci < nchunks; ci += nw) {
             Chunk ck;
-            issue(ck, ci, block_of(ci));
+            issue(ck, ci, block_of(ci), masked);
             consume(ck, ci, masked);
         }
     }
@@ -327,33 +337,38 @@ __device__ __forceinline__ void decode_body(const DecodeParams &P, const int s, 
 template <int DT, int D, int B, int W, int U, int MODE>
 __global__ __launch_bounds__(W *kWave) PA_OCC_ATTR void pa_decode_kernel(const DecodeParams P)
 {
-    // grid index: head fastest, then partition, then sequence
+    // grid index: head fastest, then sequence, then partition - the heads of a sequence start
+    // together and read neighbouring tiles, and the (sequence, partition) pairs past a sequence's
+    // end, which only exit, gather towards the end of the launch
     int item = (int)blockIdx.x;
     const int h = item % P.H;
     item /= P.H;
-    const int part = MODE == MODE_PART ? item % P.max_parts : 0;
-    const int s = MODE == MODE_PART ? item / P.max_parts : item;
+    const int s = item % P.S;
+    const int part = item / P.S;
     decode_body<DT, D, B, W, U, MODE>(P, s, h, part);
 }
 
 // Merge of the split-context partials: out = sum_p 2^(m_p-M) a_p / sum_p 2^(m_p-M) l_p
-// with a_p the unnormalised partial sums.  One wavefront per (sequence, head);
-// lane c handles the same 16-byte output fragment as in the decode kernel.
+// with a_p the unnormalised partial sums.  A (sequence, head) row takes LPT lanes (lane c
+// handles the same 16-byte output fragment as in the decode kernel), so a wavefront merges
+// 64 / LPT rows and a workgroup of four wavefronts four times that.
+constexpr int kReduceWaves = 4;
 template <int DT, int D>
-__global__ __launch_bounds__(kWave) void pa_reduce_kernel(const DecodeParams P)
+__global__ __launch_bounds__(kReduceWaves *kWave) void pa_reduce_kernel(const DecodeParams P)
 {
     using Tr = Traits<DT>;
     constexpr int EPL = Tr::EPL;
     constexpr int LPT = D * Tr::E / 16;
-    const int c = threadIdx.x;
-    if (c >= LPT) return;
+    constexpr int ROWS = kReduceWaves * kWave / LPT;      // rows per workgroup
+    const int c = threadIdx.x % LPT;
+    const int64_t row = (int64_t)blockIdx.x * ROWS + threadIdx.x / LPT;
     const int H = P.H;
-    const int h = blockIdx.x % H;
-    const int s = blockIdx.x / H;
+    if (row >= (int64_t)P.S * H) return;
+    const int s = (int)(row / H);
     const int n = P.context_lens[s];
     int parts = (n + P.partition_size - 1) / P.partition_size;
     if (parts > P.max_parts) parts = P.max_parts;
-    const int64_t base = ((int64_t)s * H + h) * P.max_parts;
+    const int64_t base = row * P.max_parts;
     float acc[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
@@ -379,7 +394,7 @@ __global__ __launch_bounds__(kWave) void pa_reduce_kernel(const DecodeParams P)
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[e] *= inv;
     }
-    reinterpret_cast<uint4 *>(P.out)[((int64_t)s * H + h) * LPT + c] = Tr::pack(acc);
+    reinterpret_cast<uint4 *>(P.out)[row * LPT + c] = Tr::pack(acc);
 }
 
 } // namespace

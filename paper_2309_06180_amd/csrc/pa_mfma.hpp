@@ -125,7 +125,7 @@ __device__ __forceinline__ void query_cols_init(QueryCols &Q, const void *q, int
 // One tile: kt / vt point at the K and V tile in LDS (rows kKPitch / kVPitch apart), its first
 // token is position t0; `mask` = query columns that map the tile; `check` = some entry may
 // need masking (a column outside the mask, or a token past a query's limit).  V rows that
-// hold no token any query sees must have been zeroed by whoever filled the tile.
+// hold no token any query sees must be zeros (whoever fills the tile does not fetch them).
 template <int DT>
 __device__ __forceinline__ void tile_step(QueryCols &Q, const char *kt, const char *vt, int t0, uint32_t mask,
                                           bool check, float scale_log2)
@@ -184,29 +184,33 @@ __device__ __forceinline__ void tile_step(QueryCols &Q, const char *kt, const ch
 struct TileRegs {
     uint4 k[4], v[4];
 };
-__device__ __forceinline__ void tile_fetch(TileRegs &R, const char *k_cache, const char *v_cache, int64_t base)
+// (rows at or past `rows` hold no token that any query of the tile sees: they are not fetched and
+// read as zeros)
+__device__ __forceinline__ void tile_fetch(TileRegs &R, const char *k_cache, const char *v_cache, int64_t base, int rows)
 {
-    const uint32_t off = (uint32_t)(threadIdx.x & (kWave - 1)) * 16u;
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t off = (uint32_t)lane * 16u;
+    if (rows >= kTileTokens) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) R.k[j] = load16_stream(k_cache + base + off + 1024 * j);
+        for (int j = 0; j < 4; ++j) R.k[j] = load16_stream(k_cache + base + off + 1024 * j);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) R.v[j] = load16_stream(v_cache + base + off + 1024 * j);
+        for (int j = 0; j < 4; ++j) R.v[j] = load16_stream(v_cache + base + off + 1024 * j);
+    } else {
+        const int r = lane / 16;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            R.k[j] = R.v[j] = make_uint4(0, 0, 0, 0);
+            if (r + 4 * j < rows) {
+                R.k[j] = load16_stream(k_cache + base + off + 1024 * j);
+                R.v[j] = load16_stream(v_cache + base + off + 1024 * j);
+            }
+        }
+    }
 }
-// rows at or past `rows` hold no token that any query of the tile sees: their V is zeroed
-__device__ __forceinline__ void tile_store(TileRegs &R, char *kt, char *vt, int rows, bool check)
+__device__ __forceinline__ void tile_store(const TileRegs &R, char *kt, char *vt)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int r = lane / 16, c = lane % 16;
-    if (check) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool unseen = r + 4 * j >= rows;
-            R.v[j].x = unseen ? 0u : R.v[j].x;
-            R.v[j].y = unseen ? 0u : R.v[j].y;
-            R.v[j].z = unseen ? 0u : R.v[j].z;
-            R.v[j].w = unseen ? 0u : R.v[j].w;
-        }
-    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) *reinterpret_cast<uint4 *>(kt + (r + 4 * j) * kKPitch + 16 * c) = R.k[j];
 #pragma unroll
@@ -329,14 +333,14 @@ __global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))
         return ((int64_t)pb * H + h) * TILE_BYTES + (int64_t)(ti * kTileTokens % B) * ROW_BYTES;
     };
     TileRegs R;
-    if (w < ntiles) tile_fetch(R, P.k_cache, P.v_cache, base_of(w, block_of(w)));
+    if (w < ntiles) tile_fetch(R, P.k_cache, P.v_cache, base_of(w, block_of(w)), t_hi - w * kTileTokens);
     int pb_next = block_of(w + W);
     for (int ti = w; ti < ntiles; ti += W) {
         const int t0 = ti * kTileTokens;
         // masking starts where the tile reaches past what the first query sees
         const bool check = t0 + kTileTokens > t_lo;
-        tile_store(R, kt, vt, t_hi - t0, check);
-        if (ti + W < ntiles) tile_fetch(R, P.k_cache, P.v_cache, base_of(ti + W, pb_next));
+        tile_store(R, kt, vt);
+        if (ti + W < ntiles) tile_fetch(R, P.k_cache, P.v_cache, base_of(ti + W, pb_next), t_hi - (ti + W) * kTileTokens);
         pb_next = block_of(ti + 2 * W);
         __builtin_amdgcn_wave_barrier();
         tile_step<DT>(Q, kt, vt, t0, 0xffffu, check, P.scale_log2);
@@ -394,14 +398,13 @@ __global__ __launch_bounds__(4 * kWave) __attribute__((amdgpu_waves_per_eu(4, 8)
 #pragma unroll
         for (int u = 0; u < STEP; ++u) {
             const int t0 = (st * STEP + u) * kTileTokens;
+            // rows that no query of the workgroup sees are not fetched and read as zeros
             rk[u] = rv[u] = make_uint4(0, 0, 0, 0);
-            if (t0 < wg_hi) {                       // uniform over the workgroup
-                const int pb = table[t0 / B];
+            if (t0 + r16 < wg_hi) {
+                const int pb = table[t0 / B];       // t0 is uniform over the workgroup
                 const int64_t off = ((int64_t)pb * H + h) * TILE_BYTES + (int64_t)(t0 % B + r16) * ROW_BYTES + 16 * c;
                 rk[u] = load16_stream(P.k_cache + off);
                 rv[u] = load16_stream(P.v_cache + off);
-                // rows at or past the context hold no token: zero V, K is masked by the logits
-                if (t0 + r16 >= n) rv[u] = make_uint4(0, 0, 0, 0);
             }
         }
     };
@@ -495,18 +498,19 @@ __device__ __forceinline__ void group_item(const DecodeParams &P, const int s0, 
     auto base_of = [&](int wi, const int4 &ent) -> int64_t {
         return ((int64_t)ent.x * H + h) * TILE_BYTES + (int64_t)(wi % SUBS) * kTileTokens * ROW_BYTES;
     };
+    // token rows of tile wi that anybody sees
+    auto rows_of = [&](int wi, const int4 &ent) -> int { return ent.w - (wi % SUBS) * kTileTokens; };
     TileRegs R;
     int4 ent = entry_of(w);
-    if (w < nwork) tile_fetch(R, P.k_cache, P.v_cache, base_of(w, ent));
+    if (w < nwork) tile_fetch(R, P.k_cache, P.v_cache, base_of(w, ent), rows_of(w, ent));
     int4 ent_next = entry_of(w + W);
     for (int wi = w; wi < nwork; wi += W) {
         const int sub = wi % SUBS;
         const uint32_t mask = (uint32_t)ent.y & 0xffffu;
         const bool ragged = ((uint32_t)ent.y >> 16) & 1u;      // some member of the set sees only part of the block
-        const int rows = ent.w - sub * kTileTokens;            // token rows of this tile that anybody sees
         const int t0 = ent.z * B + sub * kTileTokens;
-        tile_store(R, kt, vt, rows, rows < kTileTokens);
-        if (wi + W < nwork) tile_fetch(R, P.k_cache, P.v_cache, base_of(wi + W, ent_next));
+        tile_store(R, kt, vt);
+        if (wi + W < nwork) tile_fetch(R, P.k_cache, P.v_cache, base_of(wi + W, ent_next), rows_of(wi + W, ent_next));
         ent = ent_next;
         ent_next = entry_of(wi + 2 * W);
         __builtin_amdgcn_wave_barrier();
