@@ -224,8 +224,29 @@ def short_batches(pa, W, np, torch, dev):
                      "frac_of_peak": kv / us / 1e3 / HBM_PEAK_GBPS, "query_tokens_per_s": S / us * 1e6,
                      "fits_infinity_cache": bool(kv < 256e6)})
         del kc, vc
+    # one long sequence among short ones: the launch is planned from the longest context, so the short
+    # items run in workgroups sized for the long one; compare with the two parts run on their own
+    rng = np.random.default_rng(77)
+    short = rng.integers(1, 65, size=255)
+    mixed = {}
+    for name, lens in (("mixed_1x2048_255xU64", np.concatenate([[2048], short])), ("long_only", np.array([2048])),
+                       ("short_only", short)):
+        S = len(lens)
+        w = W.independent_sequences(name, "f16", H, D, B, lens, 2)
+        kc = torch.randn((w.num_blocks, H, B, D), dtype=torch.float16, device=dev)
+        vc = torch.randn_like(kc)
+        q = torch.randn((S, H, D), dtype=torch.float16, device=dev)
+        out = torch.empty_like(q)
+        bt = torch.from_numpy(w.block_tables).to(dev)
+        cl = torch.from_numpy(w.context_lens).to(dev)
+        ws = torch.empty(max(16, pa.pa_decode_workspace_bytes(S, H, D, B, w.max_context_len, pa.PA_PARTITION_AUTO)),
+                         dtype=torch.uint8, device=dev)
+        mixed[name] = {"us": _time_us(lambda: pa.pa_decode(out, q, kc, vc, bt, cl, B, float(w.scale), w.max_context_len,
+                                                           pa.PA_PARTITION_AUTO, ws), 100, torch),
+                       "kv_MB": w.kv_bytes_logical() / 1e6}
+    mixed["mixed_over_sum_of_parts"] = mixed["mixed_1x2048_255xU64"]["us"] / (mixed["long_only"]["us"] + mixed["short_only"]["us"])
     print(json.dumps({"metric": "pa_decode_short_batches", "workload": "OPT-13B shape, fp16, B=16, ctx U{1..max_len}",
-                      "rows": rows}))
+                      "rows": rows, "mixed_batch": mixed}))
 
 
 def shared_prefix(pa, W, np, torch, dev):

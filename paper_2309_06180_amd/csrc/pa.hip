@@ -31,6 +31,7 @@
 #include <string.h>
 
 #include <atomic>
+#include <tuple>
 #include <type_traits>
 
 #include "pa.h"
@@ -74,6 +75,26 @@ pa_status static_scratch(void **ptr)
 }
 
 // ---- host side -----------------------------------------------------------------
+// Kernel launches report their own status: the return value of hipLaunchKernel, kept per
+// thread between the entry and the exit of one library call.  (hipGetLastError would also
+// return, and clear, an error that an earlier call of the caller left behind.)
+thread_local hipError_t t_launch_status = hipSuccess;
+
+template <typename... KArgs, typename... Args>
+void launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t stream, Args... args)
+{
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "one argument per kernel parameter");
+    std::tuple<std::remove_cv_t<KArgs>...> vals(static_cast<std::remove_cv_t<KArgs>>(args)...);
+    void *ptrs[sizeof...(KArgs)];
+    size_t i = 0;
+    std::apply([&](auto &...v) { ((ptrs[i++] = static_cast<void *>(&v)), ...); }, vals);
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, 0, stream);
+    if (e != hipSuccess && t_launch_status == hipSuccess) t_launch_status = e;
+}
+
+void launches_begin() { t_launch_status = hipSuccess; }
+pa_status launches_end() { return t_launch_status == hipSuccess ? PA_OK : PA_ERR_HIP; }
+
 int elem_bytes(pa_dtype dt) { return dt == PA_F32 ? 4 : 2; }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -100,12 +121,9 @@ enum SharedSteps { SHARED_PLAN = 1, SHARED_DECODE = 2 };
 template <int DT, int D, int B, int W, int MODE>
 void launch_decode_kernel(const DecodeArgs &a, unsigned items)
 {
-#ifndef PA_EXP_U
-#define PA_EXP_U kChunksPerTrip
-#endif
-    hipLaunchKernelGGL((pa_decode_kernel<DT, D, B, W, MODE == MODE_PART ? kPartChunksPerTrip : PA_EXP_U, MODE>),
+    launch((pa_decode_kernel<DT, D, B, W, MODE == MODE_PART ? kPartChunksPerTrip : kChunksPerTrip, MODE>),
                        dim3(items * (unsigned)a.p.H),
-                       dim3(W * kWave), 0, a.stream, a.p);
+                       dim3(W * kWave), a.stream, a.p);
 }
 
 enum PlanMode { PLAN_SINGLE = 0, PLAN_PART = 1, PLAN_SHARED = 2 };
@@ -118,18 +136,18 @@ void launch_shared(const DecodeArgs &a)
     if constexpr (DT != PA_F32 && D == 128 && B % 16 == 0) {
         const unsigned S = (unsigned)a.p.S;
         if (a.steps & SHARED_PLAN)
-            hipLaunchKernelGGL(shared_plan_kernel, dim3(kPlanBlocks), dim3(kPlanThreads), 0, a.stream, a.p.block_tables,
+            launch(shared_plan_kernel, dim3(kPlanBlocks), dim3(kPlanThreads), a.stream, a.p.block_tables,
                                a.p.max_blocks, a.p.context_lens, a.p.S, B, const_cast<int32_t *>(a.p.ginfo),
                                const_cast<int4 *>(a.p.tiles));
         if (!(a.steps & SHARED_DECODE)) return;
         // groups + singles <= S: one workgroup per (sequence, head) always suffices
         const dim3 grid(S * (unsigned)a.p.H);
         if (a.waves >= 16)
-            hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 16>), grid, dim3(16 * kWave), 0, a.stream, a.p);
+            launch((pa_shared_fused_kernel<DT, B, 16>), grid, dim3(16 * kWave), a.stream, a.p);
         else if (a.waves >= 8)
-            hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 8>), grid, dim3(8 * kWave), 0, a.stream, a.p);
+            launch((pa_shared_fused_kernel<DT, B, 8>), grid, dim3(8 * kWave), a.stream, a.p);
         else
-            hipLaunchKernelGGL((pa_shared_fused_kernel<DT, B, 4>), grid, dim3(4 * kWave), 0, a.stream, a.p);
+            launch((pa_shared_fused_kernel<DT, B, 4>), grid, dim3(4 * kWave), a.stream, a.p);
     }
 }
 
@@ -144,13 +162,12 @@ void dispatch_mode(const DecodeArgs &a, int mode)
         else
             launch_decode_kernel<DT, D, B, 4, MODE_PART>(a, S * (unsigned)a.p.max_parts);
         constexpr unsigned kRowsPerGroup = kReduceWaves * kWave / (D * (DT == PA_F32 ? 4 : 2) / 16);
-        hipLaunchKernelGGL((pa_reduce_kernel<DT, D>), dim3((rows + kRowsPerGroup - 1) / kRowsPerGroup),
-                           dim3(kReduceWaves * kWave), 0, a.stream, a.p);
+        launch((pa_reduce_kernel<DT, D>), dim3((rows + kRowsPerGroup - 1) / kRowsPerGroup),
+                           dim3(kReduceWaves * kWave), a.stream, a.p);
     } else if (mode == PLAN_SHARED) {
         launch_shared<DT, D, B>(a);
     } else {
         switch (a.waves) {
-        case 1: launch_decode_kernel<DT, D, B, 1, MODE_SINGLE>(a, S); break;
         case 2: launch_decode_kernel<DT, D, B, 2, MODE_SINGLE>(a, S); break;
         case 4: launch_decode_kernel<DT, D, B, 4, MODE_SINGLE>(a, S); break;
         case 8: launch_decode_kernel<DT, D, B, 8, MODE_SINGLE>(a, S); break;
@@ -215,9 +232,6 @@ int chunk_tokens(pa_dtype dt, int D, int B)
 int waves_for(int tokens_per_item, int ct)
 {
     const int chunks = (tokens_per_item + ct - 1) / ct;
-#ifdef PA_EXP_SHORTW
-    if (chunks <= 16) return PA_EXP_SHORTW;
-#endif
     if (chunks <= 4) return 2;
     if (chunks <= 16) return 4;
     if (chunks <= 32) return 8;
@@ -252,14 +266,14 @@ void launch_multi_b(const DecodeArgs &a, int max_q_len)
         // shape, 64 sequences of up to 2048 tokens: 178 us against 185 us with eight)
         const dim3 grid((unsigned)a.p.S * (unsigned)a.p.H);
         if (a.waves >= 16)
-            hipLaunchKernelGGL((pa_multi_split_kernel<DT, B, 16>), grid, dim3(16 * kWave), 0, a.stream, a.p);
+            launch((pa_multi_split_kernel<DT, B, 16>), grid, dim3(16 * kWave), a.stream, a.p);
         else if (a.waves >= 8)
-            hipLaunchKernelGGL((pa_multi_split_kernel<DT, B, 8>), grid, dim3(8 * kWave), 0, a.stream, a.p);
+            launch((pa_multi_split_kernel<DT, B, 8>), grid, dim3(8 * kWave), a.stream, a.p);
         else
-            hipLaunchKernelGGL((pa_multi_split_kernel<DT, B, 4>), grid, dim3(4 * kWave), 0, a.stream, a.p);
+            launch((pa_multi_split_kernel<DT, B, 4>), grid, dim3(4 * kWave), a.stream, a.p);
     } else {
         const unsigned blocks = (unsigned)a.p.S * (unsigned)a.p.q_blocks * (unsigned)a.p.H;
-        hipLaunchKernelGGL((pa_multi_block_kernel<DT, B>), dim3(blocks), dim3(4 * kWave), 0, a.stream, a.p);
+        launch((pa_multi_block_kernel<DT, B>), dim3(blocks), dim3(4 * kWave), a.stream, a.p);
     }
 }
 
@@ -357,6 +371,7 @@ static pa_status decode_core(void *out, const void *q, const void *k_cache, cons
         partition_size = workspace ? auto_partition(num_seqs, num_heads, max_context_len) : 0;
     if (partition_size >= max_context_len) partition_size = 0;   // one range: plain single pass
 
+    launches_begin();
     DecodeArgs a;
     memset(&a, 0, sizeof(a));
     fill_common(a, out, q, k_cache, v_cache, block_tables, max_blocks_per_seq, context_lens, num_seqs,
@@ -378,7 +393,7 @@ static pa_status decode_core(void *out, const void *q, const void *k_cache, cons
     }
     if (!dispatch_decode(a, dtype, head_dim, block_size, partition_size > 0 ? PLAN_PART : PLAN_SINGLE))
         return PA_ERR_UNSUPPORTED;
-    return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
+    return launches_end();
 }
 
 pa_status pa_decode(void *out, const void *q, const void *k_cache, const void *v_cache,
@@ -448,6 +463,7 @@ static pa_status decode_shared_steps(int steps, void *out, const void *q, const 
     if (!workspace || workspace_bytes < need) return PA_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PA_ERR_ALIGN;
 
+    launches_begin();
     DecodeArgs a;
     memset(&a, 0, sizeof(a));
     fill_common(a, out, q, k_cache, v_cache, block_tables, max_blocks_per_seq, context_lens, num_seqs,
@@ -458,7 +474,7 @@ static pa_status decode_shared_steps(int steps, void *out, const void *q, const 
     a.p.ginfo = static_cast<const int32_t *>(workspace);
     a.p.tiles = reinterpret_cast<const int4 *>(static_cast<const char *>(workspace) + ginfo_bytes(num_seqs));
     if (!dispatch_decode(a, dtype, head_dim, block_size, PLAN_SHARED)) return PA_ERR_UNSUPPORTED;
-    return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
+    return launches_end();
 }
 
 pa_status pa_decode_shared(void *out, const void *q, const void *k_cache, const void *v_cache,
@@ -515,6 +531,7 @@ pa_status pa_decode_multi(void *out, const void *q, const void *k_cache, const v
     const int64_t q_blocks = max_q_len <= 16 ? 1 : (max_q_len + 63) / 64;
     const int64_t blocks = (int64_t)num_seqs * q_blocks * num_heads;
     if (blocks > 0x7fffffff) return PA_ERR_SHAPE;
+    launches_begin();
     DecodeArgs a;
     memset(&a, 0, sizeof(a));
     fill_common(a, out, q, k_cache, v_cache, block_tables, max_blocks_per_seq, context_lens, num_seqs,
@@ -525,7 +542,7 @@ pa_status pa_decode_multi(void *out, const void *q, const void *k_cache, const v
     const bool ok = dtype == PA_F16 ? launch_multi<PA_F16>(a, block_size, max_q_len)
                                     : launch_multi<PA_BF16>(a, block_size, max_q_len);
     if (!ok) return PA_ERR_UNSUPPORTED;
-    return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
+    return launches_end();
 }
 
 pa_status pa_reshape_and_cache(const void *k, const void *v, void *k_cache, void *v_cache,
@@ -541,18 +558,19 @@ pa_status pa_reshape_and_cache(const void *k, const void *v, void *k_cache, void
     if (num_tokens == 0) return PA_OK;
     if (!k || !v || !k_cache || !v_cache || !slot_mapping) return PA_ERR_NULL;
     if (!aligned16(k) || !aligned16(v) || !aligned16(k_cache) || !aligned16(v_cache)) return PA_ERR_ALIGN;
+    launches_begin();
     const int32_t frags_per_row = row_bytes / 16;
     const int64_t frags_per_token = (int64_t)frags_per_row * num_heads;
     if (frags_per_token > 0x7fffffff) return PA_ERR_SHAPE;
     const int64_t total = frags_per_token * num_tokens;
     const int64_t groups = (total + 255) / 256;
     if (groups > 0x7fffffff) return PA_ERR_SHAPE;
-    hipLaunchKernelGGL(reshape_and_cache_kernel, dim3((unsigned)groups, 2), dim3(256), 0,
+    launch(reshape_and_cache_kernel, dim3((unsigned)groups, 2), dim3(256),
                        static_cast<hipStream_t>(stream), static_cast<const uint4 *>(k),
                        static_cast<const uint4 *>(v), static_cast<uint4 *>(k_cache),
                        static_cast<uint4 *>(v_cache), slot_mapping, total, (int32_t)frags_per_token,
                        frags_per_row, block_size);
-    return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
+    return launches_end();
 }
 
 pa_status pa_copy_blocks(void *const *k_caches, void *const *v_caches, int32_t num_layers,
@@ -572,6 +590,7 @@ pa_status pa_copy_blocks(void *const *k_caches, void *const *v_caches, int32_t n
         if (!k_caches[l] || !v_caches[l]) return PA_ERR_NULL;
         if (!aligned16(k_caches[l]) || !aligned16(v_caches[l])) return PA_ERR_ALIGN;
     }
+    launches_begin();
     const int64_t frags = block_bytes / 16;
     const unsigned slices = (unsigned)((frags + 255) / 256);
     for (int l0 = 0; l0 < num_layers; l0 += kMaxCopyPtrs / 2) {
@@ -584,9 +603,9 @@ pa_status pa_copy_blocks(void *const *k_caches, void *const *v_caches, int32_t n
         }
         for (int p0 = 0; p0 < num_pairs; p0 += kMaxPairsPerLaunch) {
             const int np = num_pairs - p0 < kMaxPairsPerLaunch ? num_pairs - p0 : kMaxPairsPerLaunch;
-            hipLaunchKernelGGL(copy_blocks_kernel, dim3(slices, (unsigned)np, (unsigned)(2 * nl)), dim3(256), 0,
+            launch(copy_blocks_kernel, dim3(slices, (unsigned)np, (unsigned)(2 * nl)), dim3(256),
                                static_cast<hipStream_t>(stream), ptrs, src_dst_pairs + 2 * (int64_t)p0, frags);
-            if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
+            if (launches_end() != PA_OK) return PA_ERR_HIP;
         }
     }
     return PA_OK;
@@ -612,6 +631,7 @@ pa_status pa_swap_blocks(void *const *src_k_caches, void *const *src_v_caches,
             !aligned16(dst_v_caches[l]))
             return PA_ERR_ALIGN;
     }
+    launches_begin();
     const int64_t frags = block_bytes / 16;
     const unsigned slices = (unsigned)((frags + 255) / 256);
     for (int l0 = 0; l0 < num_layers; l0 += kMaxSwapLayers) {
@@ -626,9 +646,9 @@ pa_status pa_swap_blocks(void *const *src_k_caches, void *const *src_v_caches,
         }
         for (int p0 = 0; p0 < num_pairs; p0 += kMaxPairsPerLaunch) {
             const int np = num_pairs - p0 < kMaxPairsPerLaunch ? num_pairs - p0 : kMaxPairsPerLaunch;
-            hipLaunchKernelGGL(swap_blocks_kernel, dim3(slices, (unsigned)np, (unsigned)(2 * nl)), dim3(256), 0,
+            launch(swap_blocks_kernel, dim3(slices, (unsigned)np, (unsigned)(2 * nl)), dim3(256),
                                static_cast<hipStream_t>(stream), ptrs, src_dst_pairs + 2 * (int64_t)p0, frags);
-            if (hipGetLastError() != hipSuccess) return PA_ERR_HIP;
+            if (launches_end() != PA_OK) return PA_ERR_HIP;
         }
     }
     return PA_OK;
@@ -713,13 +733,14 @@ pa_status pa_stream_read(const void *src, size_t bytes, void *sink, void *stream
     if (!src || !sink) return PA_ERR_NULL;
     if (bytes == 0 || bytes % 16) return PA_ERR_SHAPE;
     if (!aligned16(src)) return PA_ERR_ALIGN;
+    launches_begin();
     const int64_t frags = (int64_t)(bytes / 16);
     const int64_t groups = (frags + kProbeTileFrags - 1) / kProbeTileFrags;
     if (groups > 0x7fffffff) return PA_ERR_SHAPE;
-    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)groups), dim3(256), 0,
+    launch(stream_read_kernel, dim3((unsigned)groups), dim3(256),
                        static_cast<hipStream_t>(stream), static_cast<const char *>(src), frags,
                        static_cast<uint32_t *>(sink));
-    return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
+    return launches_end();
 }
 
 } // extern "C"

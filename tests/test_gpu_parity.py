@@ -490,6 +490,70 @@ def test_copy_blocks_many_layers_two_launches(pa):
         assert same_bits(dks[l], ks[l], "f16") and same_bits(dvs[l], vs[l], "f16")
 
 
+def test_copy_and_swap_blocks_longer_pair_lists_than_one_launch(pa):
+    # a launch carries at most 65 535 pairs in its grid: longer lists take several launches
+    rng = np.random.default_rng(29)
+    N, H, B, D = 70000, 1, 8, 16                              # 256-byte blocks
+    NB = 2 * N + 7
+    k = W.to_storage(rng.standard_normal((NB, H, B, D)).astype(np.float32), "f16")
+    v = W.to_storage(rng.standard_normal((NB, H, B, D)).astype(np.float32), "f16")
+    perm = rng.permutation(NB)
+    pairs = np.stack([perm[:N], perm[N:2 * N]], axis=1).astype(np.int64)
+    dk, dv = to_dev(k), to_dev(v)
+    pa.pa_copy_blocks([dk], [dv], to_dev(pairs))
+    torch.cuda.synchronize()
+    oracle.copy_blocks([k], [v], pairs, "f16")
+    assert same_bits(dk, k, "f16") and same_bits(dv, v, "f16")
+    # the same list as a swap into a second pool on the device
+    k2, v2 = np.zeros_like(k), np.zeros_like(v)
+    dk2, dv2 = to_dev(k2), to_dev(v2)
+    pa.pa_swap_blocks([dk], [dv], [dk2], [dv2], to_dev(pairs))
+    torch.cuda.synchronize()
+    oracle.swap_blocks([k], [v], [k2], [v2], pairs, "f16")
+    assert same_bits(dk2, k2, "f16") and same_bits(dv2, v2, "f16")
+
+
+def test_an_earlier_hip_error_of_the_caller_is_not_reported_as_ours(pa):
+    # the caller provokes a HIP error of its own (a copy with an invalid direction); the next library calls
+    # must still report their own launches' status
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+    buf = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+    assert hip.hipMemcpy(buf.data_ptr(), buf.data_ptr() + 512, 16, 99) != 0
+    src = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(65536, dtype=torch.int32, device="cuda")
+    pa.pa_stream_read(src, sink)                              # raises on a non-zero status
+    w = W.config1()
+    dw = DeviceWorkload(w, W.make_values(w))
+    gpu_cache_ops(pa, dw)
+    gpu_decode(pa, dw, 0)
+    hip.hipGetLastError()                                     # leave no error behind for the tests that follow
+
+
+def test_infinity_in_unused_slots_is_ignored(pa):
+    # every slot that holds no token carries +Inf or -Inf instead of NaN: 0 * Inf would be NaN just the same
+    for w in (W.config2(seed=17, num_seqs=9, max_len=300, H=3), W.config4(seed=18, num_seqs=7, H=2),
+              W.config3(seed=19, num_groups=3, H=2, prompt_median=60, prompt_cap=200, max_out=50)):
+        v = W.make_values(w)
+        bits = {"f16": (0x7C00, 0xFC00), "bf16": (0x7F80, 0xFF80)}[w.dtype]
+        for cache in (v.k_cache, v.v_cache):
+            raw = cache.view(np.uint16)
+            hole = np.broadcast_to((~w.init_filled)[:, None, :, None], raw.shape)
+            alt = (np.arange(raw.size, dtype=np.uint32).reshape(raw.shape) & 1).astype(bool)
+            raw[hole & alt] = bits[0]
+            raw[hole & ~alt] = bits[1]
+        dw = DeviceWorkload(w, v)
+        gpu_cache_ops(pa, dw)
+        kc, vc = oracle_cache_ops(w, v)
+        ref = oracle.decode(v.q, kc, vc, w.block_tables, w.context_lens, w.scale, w.dtype)
+        assert np.isfinite(ref).all()
+        for ps in (0, 64, SHARED):
+            out = out_to_f64(gpu_decode_shared(pa, dw) if ps == SHARED else gpu_decode(pa, dw, ps), w.dtype)
+            assert np.isfinite(out).all(), "%s ps=%s: Inf leaked" % (w.name, ps)
+            assert np.abs(out - ref).max() <= TOL[w.dtype]
+
+
 def test_swap_blocks_to_pinned_host_and_back(pa):
     # Sec. 4.5: evicted blocks go to a CPU pool (pinned, device-addressable) and return to other blocks
     rng = np.random.default_rng(24)
