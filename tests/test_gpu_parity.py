@@ -515,20 +515,31 @@ def test_copy_and_swap_blocks_longer_pair_lists_than_one_launch(pa):
 
 def test_an_earlier_hip_error_of_the_caller_is_not_reported_as_ours(pa):
     # the caller provokes a HIP error of its own (a copy with an invalid direction); the next library calls
-    # must still report their own launches' status
+    # must still report their own launches' status.  Everything is allocated beforehand: torch checks the
+    # last error after its own launches.
     import ctypes
     hip = ctypes.CDLL("libamdhip64.so")
     hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
     buf = torch.zeros(1024, dtype=torch.uint8, device="cuda")
-    assert hip.hipMemcpy(buf.data_ptr(), buf.data_ptr() + 512, 16, 99) != 0
     src = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
     sink = torch.zeros(65536, dtype=torch.int32, device="cuda")
-    pa.pa_stream_read(src, sink)                              # raises on a non-zero status
     w = W.config1()
-    dw = DeviceWorkload(w, W.make_values(w))
+    v = W.make_values(w)
+    dw = DeviceWorkload(w, v)
     gpu_cache_ops(pa, dw)
-    gpu_decode(pa, dw, 0)
-    hip.hipGetLastError()                                     # leave no error behind for the tests that follow
+    out = torch.zeros_like(dw.q)
+    torch.cuda.synchronize()
+    try:
+        assert hip.hipMemcpy(buf.data_ptr(), buf.data_ptr() + 512, 16, 99) != 0
+        pa.pa_stream_read(src, sink)                          # raises on a non-zero status
+        pa.pa_decode(out, dw.q, dw.k_cache, dw.v_cache, dw.block_tables, dw.context_lens, w.block_size, float(w.scale),
+                     w.max_context_len)
+    finally:
+        hip.hipGetLastError()                                 # leave no error behind for the tests that follow
+    torch.cuda.synchronize()
+    kc, vc = oracle_cache_ops(w, v)
+    ref = oracle.decode(v.q, kc, vc, w.block_tables, w.context_lens, w.scale, w.dtype)
+    assert np.abs(out_to_f64(out, w.dtype) - ref).max() <= TOL[w.dtype]
 
 
 def test_infinity_in_unused_slots_is_ignored(pa):
