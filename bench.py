@@ -327,7 +327,20 @@ def cfg5_full_step(pa, W, np, torch, dev, steps):
     print(json.dumps(res))
 
 
-def multi_query(pa, W, np, torch, dev, q_lens=(1, 4, 16, 64, 256)):
+def calibration_copy(pa, torch, dev, H=40, B=16, D=128, dtype=None):
+    """A plain copy of known size (2048 whole blocks of K and of V, disjoint sources and destinations) for
+    hardware-counter runs to scale FETCH_SIZE / WRITE_SIZE by."""
+    dtype = dtype or torch.float16
+    ck = torch.zeros((4096, H, B, D), dtype=dtype, device=dev)
+    cv = torch.zeros((4096, H, B, D), dtype=dtype, device=dev)
+    pr = torch.stack([torch.arange(0, 2048), torch.arange(2048, 4096)], dim=1).to(torch.int64).to(dev)
+    pa.pa_copy_blocks([ck], [cv], pr)
+    torch.cuda.synchronize()
+    nbytes = 2 * 2048 * H * B * D * ck.element_size()
+    return {"kernel": "copy_blocks_kernel", "bytes_read": nbytes, "bytes_written": nbytes}
+
+
+def multi_query(pa, W, np, torch, dev, q_lens=(1, 4, 16, 64, 256), calibrate=False):
     """pa_decode_multi at the OPT-13B layer shape: every sequence brings its last min(ctx, q_len) tokens as
     queries.  Per row a roofline: algorithmic bytes = K and V of every cached token once + q in + out;
     algorithmic flops = 4*D per (query, visible token) pair (both products, causal).  The bound is the one
@@ -367,9 +380,12 @@ def multi_query(pa, W, np, torch, dev, q_lens=(1, 4, 16, 64, 256)):
     o1 = torch.empty_like(q1)
     us = _time_us(lambda: pa.pa_decode(o1, q1, kc, vc, bt, cl, B, float(w.scale), w.max_context_len, 0, None),
                   50, torch)
-    print(json.dumps({"metric": "pa_decode_multi", "workload": "OPT-13B shape, 64 seq, ctx U{1..2048}, fp16, "
-                      "q_len = min(ctx, max_q_len)", "rows": rows,
-                      "pa_decode_one_query": {"us": us, "kv_GBps": w.kv_bytes_logical() / us / 1e3}}))
+    res = {"metric": "pa_decode_multi", "workload": "OPT-13B shape, 64 seq, ctx U{1..2048}, fp16, "
+           "q_len = min(ctx, max_q_len)", "rows": rows,
+           "pa_decode_one_query": {"us": us, "kv_GBps": w.kv_bytes_logical() / us / 1e3}}
+    if calibrate:
+        res["calibration_copy"] = calibration_copy(pa, torch, dev)
+    print(json.dumps(res))
 
 
 def cache_ops(pa, np, torch, dev):
@@ -518,7 +534,7 @@ def main():
     if args.shared_prefix:
         return shared_prefix(pa, W, np, torch, dev)
     if args.multi_query:
-        return multi_query(pa, W, np, torch, dev, tuple(int(x) for x in args.q_lens.split(",")))
+        return multi_query(pa, W, np, torch, dev, tuple(int(x) for x in args.q_lens.split(",")), args.calibrate_copy)
     if args.cfg5_full_step:
         return cfg5_full_step(pa, W, np, torch, dev, min(args.steps, 10))
 
@@ -599,17 +615,7 @@ def main():
     # plus q in and out once
     algo_bytes = kv_unique + 2 * S * H * D * w.elem_bytes
 
-    calib = None
-    if args.calibrate_copy:
-        # plain copy of known size: 2048 whole blocks of K and of V, disjoint sources and destinations
-        ck = torch.zeros((4096, H, B, D), dtype=d_kc.dtype, device=dev)
-        cv = torch.zeros((4096, H, B, D), dtype=d_kc.dtype, device=dev)
-        pr = torch.stack([torch.arange(0, 2048), torch.arange(2048, 4096)], dim=1).to(torch.int64).to(dev)
-        pa.pa_copy_blocks([ck], [cv], pr)
-        torch.cuda.synchronize()
-        calib = {"kernel": "copy_blocks_kernel", "bytes_read": 2 * 2048 * H * B * D * w.elem_bytes,
-                 "bytes_written": 2 * 2048 * H * B * D * w.elem_bytes}
-        del ck, cv
+    calib = calibration_copy(pa, torch, dev, H, B, D, d_kc.dtype) if args.calibrate_copy else None
 
     run_step = step
     if args.launch == "graph":

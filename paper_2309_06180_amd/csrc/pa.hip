@@ -273,7 +273,10 @@ void launch_multi_b(const DecodeArgs &a, int max_q_len)
             launch((pa_multi_split_kernel<DT, B, 4>), grid, dim3(4 * kWave), a.stream, a.p);
     } else {
         const unsigned blocks = (unsigned)a.p.S * (unsigned)a.p.q_blocks * (unsigned)a.p.H;
-        launch((pa_multi_block_kernel<DT, B>), dim3(blocks), dim3(4 * kWave), a.stream, a.p);
+        if (a.p.q_blocks == 1)
+            launch((pa_multi_block_kernel<DT, B, true>), dim3(blocks), dim3(4 * kWave), a.stream, a.p);
+        else
+            launch((pa_multi_block_kernel<DT, B, false>), dim3(blocks), dim3(4 * kWave), a.stream, a.p);
     }
 }
 

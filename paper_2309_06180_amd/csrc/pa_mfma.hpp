@@ -353,8 +353,14 @@ __global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))
 // waves of the workgroup own 16 query columns each and share every K/V tile: the workgroup
 // loads steps of two tiles into LDS together (each thread one 16-byte fragment per tile and
 // array), double-buffered, one barrier per step, with the next step's loads in flight while
-// the current one is computed.  So K/V comes from memory once per 64 queries.
-template <int DT, int B>
+// the current one is computed.  So K/V comes from memory once per 64 queries.  With several
+// blocks of queries per sequence the same K/V is wanted again soon by a neighbouring workgroup
+// (same head, so the same XCD): the loads then leave it in the caches (STREAM unset: 750 ->
+// 650 us at 256 queries per sequence; with one block per sequence streaming loads are 3% faster).
+// (Measured and not adopted: 128 queries per workgroup, two sets of 16 columns per wave sharing
+// every LDS fragment - 199 registers, two waves per SIMD: 695 us at 256 queries, 376 instead
+// of 280 us at 64.)
+template <int DT, int B, bool STREAM>
 __global__ __launch_bounds__(4 * kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) void pa_multi_block_kernel(
     const DecodeParams P)
 {
@@ -403,8 +409,13 @@ __global__ __launch_bounds__(4 * kWave) __attribute__((amdgpu_waves_per_eu(4, 8)
             if (t0 + r16 < wg_hi) {
                 const int pb = table[t0 / B];       // t0 is uniform over the workgroup
                 const int64_t off = ((int64_t)pb * H + h) * TILE_BYTES + (int64_t)(t0 % B + r16) * ROW_BYTES + 16 * c;
-                rk[u] = load16_stream(P.k_cache + off);
-                rv[u] = load16_stream(P.v_cache + off);
+                if (STREAM) {
+                    rk[u] = load16_stream(P.k_cache + off);
+                    rv[u] = load16_stream(P.v_cache + off);
+                } else {
+                    rk[u] = *reinterpret_cast<const uint4 *>(P.k_cache + off);
+                    rv[u] = *reinterpret_cast<const uint4 *>(P.v_cache + off);
+                }
             }
         }
     };

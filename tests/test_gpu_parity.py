@@ -267,7 +267,7 @@ def test_multi_query_every_width(pa):
     # q_len across the switch from the token-splitting kernel (<= 16 queries) to the 64-query
     # workgroups, with partly filled last query blocks and contexts shorter than a block of queries
     lens = [70, 200, 129, 64, 513, 48, 1000, 333]
-    for qmax in (16, 17, 31, 48, 63, 64, 65, 130):
+    for qmax in (16, 17, 31, 48, 63, 64, 65, 130, 200):
         q_lens = [min(n, qmax - (i % 3)) for i, n in enumerate(lens)]
         for dtype in ("f16", "bf16"):
             print(dtype, qmax, multi_case(pa, dtype, lens, q_lens, H=2, seed=50 + qmax))
