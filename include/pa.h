@@ -133,24 +133,41 @@ pa_status pa_decode_static(void *out, const void *q, const void *k_cache, const 
 
 /*
  * pa_decode_shared - pa_decode for batches whose sequences share physical
- * blocks (Sec. 4.4: samples of one prompt and beams of one search map their
- * common logical blocks to the same physical blocks).  Same arguments, same
- * result as pa_decode; the difference is traffic.  On the device, the library
- * compares the block tables of consecutive sequences, groups up to 8
- * neighbours that have leading blocks in common, and lists the blocks that
- * members share (each once, with the set of members that map it).  One
- * workgroup per (group, head) applies every listed K/V tile to all members
- * mapping it (on the matrix cores), streams each member's remaining, unshared
- * blocks with the ordinary single-query pass, merges the two and writes the
- * members' finished output rows.  Sequences that share nothing go through
- * the ordinary one-pass kernel in the same launch.
+ * blocks (Sec. 4.4: samples of one prompt, beams of one search and requests
+ * behind one prefix map their common logical blocks to the same physical
+ * blocks).  Same arguments, same result as pa_decode; the difference is
+ * traffic.  On the device, the library compares the block tables of
+ * consecutive sequences and ties a sequence to its predecessor when the
+ * leading full blocks they have in common are worth it: at least 32 tokens and
+ * at least one eighth of the shorter of the two contexts.  Chains of tied
+ * sequences are cut into groups of at most 16.  For every group it lists each
+ * physical block that a member maps, once, with the set of members that map
+ * it; one workgroup per (group, head) then applies every listed K/V tile to
+ * the queries of all members that map it, on the matrix cores (the members
+ * are the 16 query columns of the tiles), and writes the members' output
+ * rows.  A block is therefore read from memory once per group instead of once
+ * per reader.  Sequences outside any group go through pa_decode's one-pass
+ * kernel in the same launch.
+ *
+ * When it pays: the decode launch reads the distinct bytes of a batch at about
+ * 0.80 of the HBM peak (0.86 for pa_decode on batches without sharing), so it
+ * wins as soon as a noticeable part of the logical bytes is shared: 1.2x at
+ * the parallel-sampling configuration (a third shared), 1.9x with beams of
+ * six, 3.4x when 256 requests share a 1024-token prefix.  With nothing shared
+ * no group forms and the decode launch costs what pa_decode costs; the plan
+ * adds 10-20 us per call, which pa_shared_plan / pa_decode_shared_planned
+ * spread over the layers of a step.  A prefix of a few dozen tokens under
+ * long private contexts is not worth a group by the rule above, and a short
+ * prefix that every sequence shares (80 tokens) is served as fast out of the
+ * caches by pa_decode.
  *
  * Callers should place sequences that were forked from one another next to
  * each other in the batch; any order is correct, only sharing between
  * neighbours is exploited.  `workspace` must hold
- * pa_decode_shared_workspace_bytes(...) bytes.  Three kernels are enqueued on
- * `stream`.  2-byte types at head_dim 128 with block_size >= 16; other shapes
- * run pa_decode's one-pass kernel (same result, no saving).
+ * pa_decode_shared_workspace_bytes(...) bytes.  Two kernels are enqueued on
+ * `stream`.  2-byte types at head_dim 128 with block_size >= 16 and at most
+ * 16384 sequences; other shapes run pa_decode's one-pass kernel (same result,
+ * no saving).
  */
 pa_status pa_decode_shared(void *out, const void *q, const void *k_cache, const void *v_cache,
                            const int32_t *block_tables, int32_t max_blocks_per_seq,
@@ -166,8 +183,8 @@ size_t pa_decode_shared_workspace_bytes(int32_t num_seqs, int32_t num_heads, int
  * pa_shared_plan / pa_decode_shared_planned - pa_decode_shared in two steps.
  * Every layer of a model uses the same block tables (Sec. 4.1, one table per
  * sequence for all layers), so the grouping and the tile lists need building
- * once per decoding step, not once per layer: pa_shared_plan enqueues the two
- * preparation kernels and leaves the plan in `workspace`
+ * once per decoding step, not once per layer: pa_shared_plan enqueues the
+ * planning kernel and leaves the plan in `workspace`
  * (pa_decode_shared_workspace_bytes(...) bytes, caller-owned);
  * pa_decode_shared_planned enqueues only the decode launch and reads the plan.
  * The plan is valid for exactly the block_tables, context_lens, num_seqs,
@@ -178,6 +195,22 @@ size_t pa_decode_shared_workspace_bytes(int32_t num_seqs, int32_t num_heads, int
  * pa_decode_shared(...) is pa_shared_plan(...) followed by
  * pa_decode_shared_planned(...) on the same workspace.  For shapes that
  * pa_decode_shared passes to pa_decode, the plan is empty and never read.
+ *
+ * Layout of a plan, for inspection (S = num_seqs, MB = max_blocks_per_seq;
+ * int32 words): six arrays of S words - in_group[s] (1 if s belongs to a
+ * group), group_size[s] (members of the group that starts at s, else 0),
+ * tile_count[s] (entries on that group's tile list; defined only where a group
+ * starts), adj[s] (leading full blocks s shares with s-1), single_list[]
+ * (sequences outside any group, ascending), group_list[] (first sequences of
+ * the groups, ascending) - then group_count and single_count at words 6S and
+ * 6S+1; from the next multiple of four words at or after 6S+4, S work items of
+ * four words (kind: 2 group / 1 single sequence / 0 nothing, first sequence,
+ * members, tile-list entries): groups first, then singles, then nothing.  At
+ * the next 16-byte boundary the tile array begins: S*MB entries of four words;
+ * the list of the group that starts at s begins at entry s*MB and holds
+ * (physical block, member set in bits 0..15 | "some member sees only part of
+ * it" in bit 16, logical block index, tokens seen by the longest member of the
+ * set), ordered by logical block index.
  */
 pa_status pa_shared_plan(const int32_t *block_tables, int32_t max_blocks_per_seq,
                          const int32_t *context_lens, int32_t num_seqs, int32_t num_heads,
@@ -202,8 +235,10 @@ pa_status pa_decode_shared_planned(void *out, const void *q, const void *k_cache
  * must already be in the cache, as for pa_decode).  Query i of them, at
  * position n_s - q_len_s + i, attends to tokens 0 .. n_s - q_len_s + i
  * (causal), by the same formula as pa_decode; q_len_s = 1 is pa_decode.
- * Runs on the matrix cores, 16 queries per workgroup; K/V of a sequence is read
- * once per 16 queries.
+ * Runs on the matrix cores.  With max_q_len <= 16 one workgroup per (sequence,
+ * head) serves all of a sequence's queries and K/V is read once; beyond that
+ * one workgroup serves 64 queries and K/V is read once per 64 queries (from
+ * the caches, mostly, after the first time).
  *
  *   out, q        [q_start[S]][H][D] dtype, rows of sequence s at q_start[s] ..
  *   q_start       device [S+1] int32, non-decreasing, q_start[0] = 0
