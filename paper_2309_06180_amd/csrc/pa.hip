@@ -273,10 +273,12 @@ void launch_multi_b(const DecodeArgs &a, int max_q_len)
             launch((pa_multi_split_kernel<DT, B, 4>), grid, dim3(4 * kWave), a.stream, a.p);
     } else {
         const unsigned blocks = (unsigned)a.p.S * (unsigned)a.p.q_blocks * (unsigned)a.p.H;
-        if (a.p.q_blocks == 1)
-            launch((pa_multi_block_kernel<DT, B, true>), dim3(blocks), dim3(4 * kWave), a.stream, a.p);
+        if (max_q_len <= 64)
+            launch((pa_multi_block_kernel<DT, B, true, 1>), dim3(blocks), dim3(4 * kWave), a.stream, a.p);
+        else if (a.p.q_blocks == 1)
+            launch((pa_multi_block_kernel<DT, B, true, 2>), dim3(blocks), dim3(4 * kWave), a.stream, a.p);
         else
-            launch((pa_multi_block_kernel<DT, B, false>), dim3(blocks), dim3(4 * kWave), a.stream, a.p);
+            launch((pa_multi_block_kernel<DT, B, false, 2>), dim3(blocks), dim3(4 * kWave), a.stream, a.p);
     }
 }
 
@@ -531,7 +533,8 @@ pa_status pa_decode_multi(void *out, const void *q, const void *k_cache, const v
     if (num_seqs == 0 || max_q_len == 0) return PA_OK;
     if (!out || !q || !k_cache || !v_cache || !block_tables || !context_lens || !q_start) return PA_ERR_NULL;
     if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return PA_ERR_ALIGN;
-    const int64_t q_blocks = max_q_len <= 16 ? 1 : (max_q_len + 63) / 64;
+    // 64 queries per workgroup up to 64 per sequence, 128 beyond
+    const int64_t q_blocks = max_q_len <= 64 ? 1 : (max_q_len + 127) / 128;
     const int64_t blocks = (int64_t)num_seqs * q_blocks * num_heads;
     if (blocks > 0x7fffffff) return PA_ERR_SHAPE;
     launches_begin();

@@ -179,6 +179,180 @@ __device__ __forceinline__ void tile_step(QueryCols &Q, const char *kt, const ch
     }
 }
 
+// Two tiles at once (32 tokens), for the kernel whose tiles arrive in LDS by direct loads (rows
+// 256 bytes apart and rotated: row r keeps its 16-byte chunk q at chunk position (q + r) mod 16 in a
+// K tile and (q + 3 r) mod 16 in a V tile - the layout a direct load can produce, since it writes 16
+// bytes per lane at consecutive addresses but each lane may fetch any chunk, with the bank pattern of
+// rows 272 / 304 bytes apart).  `pair` is the LDS byte address of the
+// K tile, V tile, K tile, V tile of tokens t0 .. t0+15 and t0+16 .. t0+31 (4 KiB each); koff /
+// voff are this lane's offsets inside a K / V tile (pair_offsets).  Differences to two calls of
+// tile_step, all of them fewer vector instructions per token:
+//   - one running-maximum round per 32 tokens;
+//   - the contraction slots of the P V products are tokens 4g..4g+3 of the first tile (slots
+//     8g+0..3) and of the second (slots 8g+4..7), so the V^T operand is two transposing reads
+//     side by side, and the leading and trailing 16-bit pieces of P go through two instructions
+//     on the same V^T registers (no register copies);
+//   - f16: the factor 2^14 that keeps small weights in the range of the 16-bit pieces is part of
+//     the exponent, so it is in the running sum as well and cancels in the final division.
+constexpr float kPairShiftF16 = 14.0f;
+// An opaque 1.0f in a scalar register: p * one - (float)h is then a fused multiply-add with one 16-bit
+// operand, which the compiler issues as a single v_fma_mix_f32 (it would turn p - (float)h into a
+// conversion and a subtraction).  Vector instructions are what this kernel is bound by: measured,
+// each takes ~4.5 cycles of a SIMD's issue port (v_exp_f32 ~8, a 16x16x32 matrix instruction 8),
+// whatever the number of resident waves.  (Written as compiler-visible arithmetic, not as inline
+// assembly: the compiler places the wait states that instruction pairs such as matrix result ->
+// vector read need only around instructions it can see.)
+__device__ __forceinline__ float opaque_one()
+{
+    float one;
+    asm("s_mov_b32 %0, 1.0" : "=s"(one));
+    return one;
+}
+// LDS accesses by byte address (a 32-bit number, so that a lane offset plus a constant folds into
+// the instruction's immediate offset)
+__device__ __forceinline__ uint4 lds_read16(uint32_t at)
+{
+    typedef const u32x4_t __attribute__((address_space(3))) *lds_u4_ptr;
+    const u32x4_t v = *(lds_u4_ptr)(uintptr_t)at;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint2 lds_read8_transposed(uint32_t at)
+{
+    typedef short4_t __attribute__((address_space(3))) *lds_tr_ptr;
+    return __builtin_bit_cast(uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_tr_ptr)(uintptr_t)at));
+}
+__device__ __forceinline__ void pair_offsets(uint32_t (&koff)[4], uint32_t (&voff)[8])
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int g = lane / 16, c = lane % 16;
+    const int vrow = 4 * g + c / 4;
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) koff[cc] = (uint32_t)(c * 256 + 16 * ((g + 4 * cc + c) & 15));
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        voff[e] = (uint32_t)(vrow * 256 + 16 * ((2 * e + (c % 4) / 2 + 3 * vrow) & 15) + 8 * (c & 1));
+}
+template <int DT, int NQ>
+__device__ __forceinline__ void pair_step(QueryCols (&Q)[NQ], const uint32_t pair, const uint32_t (&koff)[4],
+                                          const uint32_t (&voff)[8], const int t0, const bool (&check)[NQ],
+                                          const float scale_log2, const float one)
+{
+    constexpr uint32_t TILE = 4096;                    // K tile | V tile | K tile | V tile
+    const int lane = threadIdx.x & (kWave - 1);
+    const int g = lane / 16;
+    // every K fragment is read once and serves the NQ sets of query columns
+    float4_t S0[NQ], S1[NQ];
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) S0[j] = S1[j] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) {
+        const uint4 k0 = lds_read16(pair + koff[cc]);
+        const uint4 k1 = lds_read16(pair + 2 * TILE + koff[cc]);
+#pragma unroll
+        for (int j = 0; j < NQ; ++j) {
+            S0[j] = mfma_k32<DT>(k0, Q[j].qf[cc], S0[j]);
+            S1[j] = mfma_k32<DT>(k1, Q[j].qf[cc], S1[j]);
+        }
+    }
+    float x[NQ][8], m_new[NQ];
+    bool moved = false;
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+        if (check[j]) {
+            // by select, never by multiplying: rows past the stored tokens may hold anything
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                S0[j][v] = (t0 + 4 * g + v <= Q[j].limit) ? S0[j][v] : -INFINITY;
+                S1[j][v] = (t0 + 16 + 4 * g + v <= Q[j].limit) ? S1[j][v] : -INFINITY;
+            }
+        }
+        // (scaled first: products of a multiplication are known to be canonical numbers, so the maxima
+        // below are one instruction each)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            x[j][v] = S0[j][v] * scale_log2;
+            x[j][4 + v] = S1[j][v] * scale_log2;
+        }
+        const float tmax = fmaxf(fmaxf(fmaxf(x[j][0], x[j][1]), fmaxf(x[j][2], x[j][3])),
+                                 fmaxf(fmaxf(x[j][4], x[j][5]), fmaxf(x[j][6], x[j][7])));
+        m_new[j] = fmaxf(Q[j].m, quad_rows_max(tmax));
+        moved = moved || m_new[j] > Q[j].m;
+    }
+    if (__any(moved)) {
+#pragma unroll
+        for (int j = 0; j < NQ; ++j) {
+            const float alpha = __builtin_amdgcn_exp2f(Q[j].m - m_new[j]);
+            Q[j].lsum *= alpha;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) Q[j].O[e][v] *= alpha;
+            }
+            Q[j].m = m_new[j];
+        }
+    }
+    // leading and trailing 16-bit pieces of the eight weights, in contraction-slot order
+    uint4 ph[NQ], pl[NQ];
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+        const float shift = (DT == PA_F16 ? kPairShiftF16 : 0.0f) - Q[j].m;
+        float p[8];
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            p[v] = __builtin_amdgcn_exp2f(x[j][v] + shift);
+            Q[j].lsum += p[v];
+        }
+        if (DT == PA_F16) {
+            typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                hi[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(p[2 * i], p[2 * i + 1]));
+                const half2v hh = __builtin_bit_cast(half2v, hi[i]);
+                lo[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(__builtin_fmaf(p[2 * i], one, -(float)hh.x),
+                                                                                 __builtin_fmaf(p[2 * i + 1], one, -(float)hh.y)));
+            }
+            ph[j] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+            pl[j] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+        } else {
+            typedef float float2v __attribute__((ext_vector_type(2)));
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                hi[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(float2v{p[2 * i], p[2 * i + 1]}, bf16x2v_t));
+                const float2v r = {p[2 * i] - as_f32(hi[i] << 16), p[2 * i + 1] - as_f32(hi[i] & 0xffff0000u)};
+                lo[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, bf16x2v_t));
+            }
+            ph[j] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+            pl[j] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+        }
+    }
+    // V^T operand of dimensions 16e .. 16e+15: tokens 4g..4g+3 of the first tile, then of the second;
+    // read once for the NQ sets.  Several operands at a time, so that the two products into one
+    // accumulator are four instructions apart.
+    constexpr int EG = NQ == 1 ? 4 : 2;
+#pragma unroll
+    for (int e4 = 0; e4 < 8; e4 += EG) {
+        uint4 va[EG];
+#pragma unroll
+        for (int i = 0; i < EG; ++i) {
+            const uint2 a = lds_read8_transposed(pair + TILE + voff[e4 + i]);
+            const uint2 b = lds_read8_transposed(pair + 3 * TILE + voff[e4 + i]);
+            va[i] = make_uint4(a.x, a.y, b.x, b.y);
+        }
+#pragma unroll
+        for (int j = 0; j < NQ; ++j) {
+#pragma unroll
+            for (int i = 0; i < EG; ++i) Q[j].O[e4 + i] = mfma_k32<DT>(va[i], ph[j], Q[j].O[e4 + i]);
+        }
+#pragma unroll
+        for (int j = 0; j < NQ; ++j) {
+#pragma unroll
+            for (int i = 0; i < EG; ++i) Q[j].O[e4 + i] = mfma_k32<DT>(va[i], pl[j], Q[j].O[e4 + i]);
+        }
+    }
+}
+
 // A tile on its way from HBM to LDS: the same coalesced 1 KiB-per-instruction loads as the
 // single-query kernel (lane 16r + c: 16 bytes at column 16c of token rows r, r+4, r+8, r+12).
 struct TileRegs {
@@ -360,16 +534,53 @@ __global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))
 // (Measured and not adopted: 128 queries per workgroup, two sets of 16 columns per wave sharing
 // every LDS fragment - 199 registers, two waves per SIMD: 695 us at 256 queries, 376 instead
 // of 280 us at 64.)
-template <int DT, int B, bool STREAM>
-__global__ __launch_bounds__(4 * kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) void pa_multi_block_kernel(
+// One 16-byte-per-lane load straight from global memory into LDS (no register staging): lane i
+// fetches from src_uniform + its own lane_offset and the data lands at lds_base + 16 i.  Completion counts
+// on vmcnt like any vector load; the compiler does not know that the instruction writes LDS, so
+// the kernel places its own waits (the "memory" clobber keeps compiler-issued LDS accesses on
+// their side of the statement).  The five idle cycles cover what the compiler cannot see either:
+// M0 written just before its use, and a base address that a vector instruction may have produced.
+template <bool STREAM>
+__device__ __forceinline__ void load16_to_lds(uint32_t lds_base, const char *src_uniform, uint32_t lane_offset)
+{
+    // (M0 carries the LDS address; it is put back afterwards because the compiler does not expect
+    // inline assembly to change it)
+    uint32_t m0_before;
+    if (STREAM)
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %2, %3 nt\n\ts_mov_b32 m0, %0"
+                     : "=&s"(m0_before)
+                     : "s"(lds_base), "v"(lane_offset), "s"(src_uniform)
+                     : "memory");
+    else
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
+                     : "=&s"(m0_before)
+                     : "s"(lds_base), "v"(lane_offset), "s"(src_uniform)
+                     : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vector_loads_but()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// NQ sets of 16 query columns per wave: 64 NQ queries per workgroup.  Every K and V^T fragment a wave
+// reads from LDS serves its NQ sets, which is what the LDS bandwidth asks for: a 16x16x32 product
+// takes 16 cycles of a SIMD and its K or V^T operand is 1 KiB of LDS reads, against 128 bytes per
+// cycle for the four SIMDs together (measured: ~100 for ds_read_b128, ~50 for the transposing read).
+template <int DT, int B, bool STREAM, int NQ>
+__global__ __launch_bounds__(4 * kWave) __attribute__((amdgpu_waves_per_eu(NQ == 1 ? 4 : 2, 8))) void pa_multi_block_kernel(
     const DecodeParams P)
 {
     using Tr = Traits<DT>;
-    constexpr int W = 4, ROW_BYTES = 256, STEP = 2;
+    typedef char __attribute__((address_space(3))) *lds_char_ptr;
+    constexpr int W = 4, ROW_BYTES = 256, STEP = 2, NS = NQ == 1 ? 2 : 4, QW = 16 * NQ, QB = W * QW;
+    constexpr int TILE_LDS = 2 * kTileTokens * ROW_BYTES;            // K tile, then V tile, rows unpadded
+    constexpr int STAGE_LDS = STEP * TILE_LDS;
+    constexpr int LOADS_PER_STEP = 2 * STEP;                         // per thread
     constexpr int64_t TILE_BYTES = (int64_t)B * ROW_BYTES;
     static_assert(DT != PA_F32 && B % kTileTokens == 0, "two-byte elements, whole 16-token tiles per block");
-    constexpr float kUnscale = DT == PA_F16 ? 1.0f / 16384.0f : 1.0f;
-    __shared__ __align__(16) char sm_stage[2][STEP][kTileLds];
+    static_assert(STEP == 2, "pair_step takes two tiles");
+    __shared__ __align__(1024) char sm_stage[NS][STAGE_LDS];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -382,92 +593,122 @@ __global__ __launch_bounds__(4 * kWave) __attribute__((amdgpu_waves_per_eu(4, 8)
     const int n = P.context_lens[s];
     const int qs = P.q_start[s];
     const int qlen = P.q_start[s + 1] - qs;
-    const int q0 = qb * 64;
+    const int q0 = qb * QB;
     if (q0 >= qlen || n <= 0) return;
-    const int wg_members = qlen - q0 < 64 ? qlen - q0 : 64;
+    const int wg_members = qlen - q0 < QB ? qlen - q0 : QB;
     const int wg_hi = n - qlen + q0 + wg_members;      // tokens the last query of the workgroup sees
     const int nsteps = (wg_hi + STEP * kTileTokens - 1) / (STEP * kTileTokens);
-    // this wave's 16 columns
-    int members = wg_members - 16 * w;
-    members = members < 0 ? 0 : (members > 16 ? 16 : members);
-    const int t_lo = n - qlen + q0 + 16 * w + 1;
-    const int t_hi = members > 0 ? t_lo + members - 1 : 0;
+    // this wave's NQ sets of 16 columns: set j holds queries q0 + QW w + 16 j + (0 .. 15)
+    QueryCols Q[NQ];
+    int members[NQ], t_lo[NQ];
+    int t_hi = 0;                                      // tokens the wave's last query sees
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+        const int first = QW * w + 16 * j;
+        int mem = wg_members - first;
+        members[j] = mem < 0 ? 0 : (mem > 16 ? 16 : mem);
+        t_lo[j] = n - qlen + q0 + first + 1;           // tokens the set's first query sees
+        if (members[j] > 0) t_hi = t_lo[j] + members[j] - 1;
+        query_cols_init<DT>(Q[j], P.q, (int64_t)qs + q0 + first + c, H, h, c < members[j], t_lo[j] - 1 + c);
+    }
+    uint32_t koff[4], voff[8];
+    pair_offsets(koff, voff);
+    const float one = opaque_one();
+    // (the table is read-only for the whole launch: through the constant address space these
+    // uniform loads go through the scalar unit and its own counter, not in line with the tile loads)
+    typedef const int32_t __attribute__((address_space(4))) *uniform_i32_ptr;
+    const uniform_i32_ptr table = (uniform_i32_ptr)(uintptr_t)(P.block_tables + (int64_t)s * P.max_blocks);
 
-    QueryCols Q;
-    query_cols_init<DT>(Q, P.q, (int64_t)qs + q0 + 16 * w + c, H, h, c < members, t_lo - 1 + c);
-    const int32_t *__restrict__ table = P.block_tables + (int64_t)s * P.max_blocks;
-
-    // thread (row r16 = tid / 16, column chunk c) moves one fragment of each tile of a step
+    // Wave w moves rows 4w .. 4w+3 of every tile: lane 16j + c fills chunk position c of LDS row
+    // r16 = 4w + j, i.e. fetches chunk (c - r16) mod 16 of a K row and (c - 3 r16) mod 16 of a V row.
+    // A row past the last token any query of the workgroup sees fetches that last token's row instead
+    // (finite data with weight zero: rows past the stored tokens may hold anything).
     const int r16 = threadIdx.x / 16;
-    uint4 rk[STEP], rv[STEP];
-    auto fetch = [&](int st) {
+    const int k_chunk = 16 * ((c - r16) & 15), v_chunk = 16 * ((c - 3 * r16) & 15);
+    const int last_tile = ((wg_hi - 1) / kTileTokens) * kTileTokens;
+    const int last_row = wg_hi - 1 - last_tile;                  // last visible row of the last visible tile
+    const uint32_t k_lane = (uint32_t)(r16 * ROW_BYTES + k_chunk), v_lane = (uint32_t)(r16 * ROW_BYTES + v_chunk);
+    const uint32_t k_lane_last = (uint32_t)((r16 < last_row ? r16 : last_row) * ROW_BYTES + k_chunk);
+    const uint32_t v_lane_last = (uint32_t)((r16 < last_row ? r16 : last_row) * ROW_BYTES + v_chunk);
+    const uint32_t lds_stage0 = (uint32_t)(uintptr_t)(lds_char_ptr)(&sm_stage[0][0]);
+    const uint32_t lds0 = lds_stage0 + (uint32_t)w * 1024u;
+    auto issue = [&](int stage, int st) {
 #pragma unroll
         for (int u = 0; u < STEP; ++u) {
-            const int t0 = (st * STEP + u) * kTileTokens;
-            // rows that no query of the workgroup sees are not fetched and read as zeros
-            rk[u] = rv[u] = make_uint4(0, 0, 0, 0);
-            if (t0 + r16 < wg_hi) {
-                const int pb = table[t0 / B];       // t0 is uniform over the workgroup
-                const int64_t off = ((int64_t)pb * H + h) * TILE_BYTES + (int64_t)(t0 % B + r16) * ROW_BYTES + 16 * c;
-                if (STREAM) {
-                    rk[u] = load16_stream(P.k_cache + off);
-                    rv[u] = load16_stream(P.v_cache + off);
-                } else {
-                    rk[u] = *reinterpret_cast<const uint4 *>(P.k_cache + off);
-                    rv[u] = *reinterpret_cast<const uint4 *>(P.v_cache + off);
+            int t0 = (st * STEP + u) * kTileTokens;            // uniform over the workgroup
+            const bool last = t0 >= last_tile;
+            t0 = last ? last_tile : t0;
+            const int pb = table[t0 / B];
+            const int64_t off = ((int64_t)pb * H + h) * TILE_BYTES + (int64_t)(t0 % B) * ROW_BYTES;   // uniform
+            const uint32_t at = lds0 + (uint32_t)(stage * STAGE_LDS + u * TILE_LDS);
+            load16_to_lds<STREAM>(at, P.k_cache + off, last ? k_lane_last : k_lane);
+            load16_to_lds<STREAM>(at + kTileTokens * ROW_BYTES, P.v_cache + off, last ? v_lane_last : v_lane);
+        }
+    };
+    // NS - 1 steps of loads are in flight while one is computed.  Every step issues its loads, also
+    // past the last one (they re-read the last tile into a stage nobody reads), so that the wait at
+    // the top of a step can name how many younger loads it leaves in flight.
+#pragma unroll
+    for (int j = 0; j < NS - 1; ++j) issue(j, j);
+    // the query fragments are needed from here on: have the compiler wait for their loads now, not
+    // at their first use inside the loop, where its wait would also drain the tile loads in flight
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) asm volatile("" ::"v"(__builtin_bit_cast(u32x4_t, Q[j].qf[cc])));
+    }
+    const float scale_log2 = P.scale_log2;
+    for (int st0 = 0; st0 < nsteps; st0 += NS) {
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            const int st = st0 + j;
+            if (st < nsteps) {                                  // uniform over the workgroup
+                wait_vector_loads_but<(NS - 2) * LOADS_PER_STEP>();   // this thread's part of step st is in LDS
+                // everyone's part is; and everyone is done with step st - 1, whose stage is loaded next
+                __syncthreads();
+                issue((j + NS - 1) % NS, st + NS - 1);
+                const int t0 = st * STEP * kTileTokens;
+                if (t0 < t_hi) {
+                    bool check[NQ];
+#pragma unroll
+                    for (int i = 0; i < NQ; ++i) check[i] = t0 + STEP * kTileTokens > t_lo[i];
+                    pair_step<DT, NQ>(Q, lds_stage0 + (uint32_t)(j * STAGE_LDS), koff, voff, t0, check, scale_log2, one);
                 }
             }
         }
-    };
-    auto stash = [&](int buf) {
-#pragma unroll
-        for (int u = 0; u < STEP; ++u) {
-            char *kt = sm_stage[buf][u];
-            *reinterpret_cast<uint4 *>(kt + r16 * kKPitch + 16 * c) = rk[u];
-            *reinterpret_cast<uint4 *>(kt + kTileTokens * kKPitch + r16 * kVPitch + 16 * c) = rv[u];
-        }
-    };
-    fetch(0);
-    for (int st = 0; st < nsteps; ++st) {
-        const int buf = st & 1;
-        stash(buf);
-        if (st + 1 < nsteps) fetch(st + 1);
-        // orders this step's LDS writes before their readers, and the reads of two steps ago
-        // (same buffer) before these writes were issued: every wave passed the previous barrier
-        // only after finishing them
-        __syncthreads();
-#pragma unroll
-        for (int u = 0; u < STEP; ++u) {
-            const int t0 = (st * STEP + u) * kTileTokens;
-            if (t0 < t_hi) {
-                const char *kt = sm_stage[buf][u];
-                tile_step<DT>(Q, kt, kt + kTileTokens * kKPitch, t0, 0xffffu, t0 + kTileTokens > t_lo, P.scale_log2);
-            }
-        }
     }
+    wait_vector_loads_but<0>();                        // the loads issued past the last step have landed
     // finished rows: through the wave's share of the (now idle) staging buffers, so that every store
     // instruction writes whole 256-byte rows
     __syncthreads();                                   // all waves are done reading the tiles
-    if (members <= 0) return;
-    const float l = quad_rows_sum(Q.lsum);
-    const float inv = (l > 0.f ? 1.0f / l : 0.f) * kUnscale;
-    constexpr int MROW = 128 + 4;
-    static_assert(W * 16 * MROW * 4 <= 2 * STEP * kTileLds, "output rows fit the staging buffers");
-    float(*const rows)[MROW] = reinterpret_cast<float(*)[MROW]>(&sm_stage[0][0][0] + w * 16 * MROW * 4);
+    // packed to the storage type first: 16 rows of 256 bytes (+16 of padding) per set
+    constexpr int OROW = ROW_BYTES + 16;
+    static_assert(W * QW * OROW <= NS * STAGE_LDS, "output rows fit the staging buffers");
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-        *reinterpret_cast<float4 *>(&rows[c][16 * e + 4 * g]) =
-            make_float4(Q.O[e][0] * inv, Q.O[e][1] * inv, Q.O[e][2] * inv, Q.O[e][3] * inv);
-    __builtin_amdgcn_wave_barrier();
+    for (int j = 0; j < NQ; ++j) {
+        if (members[j] <= 0) continue;
+        const float l = quad_rows_sum(Q[j].lsum);
+        const float inv = l > 0.f ? 1.0f / l : 0.f;     // (f16: sum and products both carry the factor 2^14)
+        char *const rows = &sm_stage[0][0] + (w * NQ + j) * 16 * OROW;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int j = g + 4 * i;                        // lane 16g + c: dimensions 8c .. 8c+7 of query j
-        if (j < members) {
-            float v8[8];
+        for (int e = 0; e < 8; e += 2) {
+            const float v8[8] = {Q[j].O[e][0] * inv,     Q[j].O[e][1] * inv,     Q[j].O[e][2] * inv,
+                                 Q[j].O[e][3] * inv,     Q[j].O[e + 1][0] * inv, Q[j].O[e + 1][1] * inv,
+                                 Q[j].O[e + 1][2] * inv, Q[j].O[e + 1][3] * inv};
+            const uint4 pk = Tr::pack(v8);
+            *reinterpret_cast<uint2 *>(rows + c * OROW + 32 * e + 8 * g) = make_uint2(pk.x, pk.y);
+            *reinterpret_cast<uint2 *>(rows + c * OROW + 32 * (e + 1) + 8 * g) = make_uint2(pk.z, pk.w);
+        }
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v8[e] = rows[j][8 * c + e];
-            char *dst = static_cast<char *>(P.out) + (((int64_t)qs + q0 + 16 * w + j) * H + h) * ROW_BYTES + 16 * c;
-            store_frag_stream(reinterpret_cast<uint4 *>(dst), __builtin_bit_cast(u32x4_t, Tr::pack(v8)));
+        for (int i = 0; i < 4; ++i) {
+            const int r = g + 4 * i;                    // lane 16g + c: bytes 16c .. 16c+15 of query r of the set
+            if (r < members[j]) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(rows + r * OROW + 16 * c);
+                char *dst = static_cast<char *>(P.out) +
+                            (((int64_t)qs + q0 + QW * w + 16 * j + r) * H + h) * ROW_BYTES + 16 * c;
+                store_frag_stream(reinterpret_cast<uint4 *>(dst), __builtin_bit_cast(u32x4_t, v));
+            }
         }
     }
 }
