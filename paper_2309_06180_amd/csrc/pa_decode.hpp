@@ -243,7 +243,8 @@ __device__ __forceinline__ void stream_range(const DecodeParams &P, const int s,
 
 // Tokens [t_begin, t_end) of sequence s against head h with all W waves of the workgroup: on
 // return wave 0's lanes with g == 0 hold m, l and acc[] of the whole range; other lanes hold
-// nothing useful.  Every wave of the workgroup must call it (it synchronises).
+// nothing useful.  Every wave of the workgroup must call it (it synchronises those with work),
+// and must not meet another workgroup barrier afterwards: waves without work have gone.
 template <int DT, int D, int B, int W, int U>
 __device__ __forceinline__ void decode_range(const DecodeParams &P, const int s, const int h, const int t_begin,
                                              const int t_end, float &m, float &l,
@@ -256,9 +257,21 @@ __device__ __forceinline__ void decode_range(const DecodeParams &P, const int s,
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int g = lane / LPT;
     const int c = lane % LPT;
+    // A range shorter than W chunks leaves waves without work.  They leave at once (a barrier waits
+    // for the surviving waves of a workgroup only), so that their slots are free for the next
+    // workgroup while this one's few busy waves stream: a launch is planned from its longest
+    // context, and in a batch of mixed lengths most items are much shorter.
+    constexpr int TPL = kWave / LPT, LPC = (B / TPL) < 4 ? (B / TPL) : 4, CT = LPC * TPL;   // as in stream_range
+    const int nchunks = (t_end - t_begin + CT - 1) / CT;
+    const int active = nchunks < W ? nchunks : W;
+    if (w >= active) {
+        m = kNegBig;
+        l = 0.f;
+        return;
+    }
     stream_range<DT, D, B, U>(P, s, h, t_begin, t_end, w, W, m, l, acc);
 
-    // merge the W waves of the workgroup through LDS
+    // merge the busy waves of the workgroup through LDS
     if (W > 1) {
         __shared__ float sm_acc[W][D];
         __shared__ float sm_m[W], sm_l[W];
@@ -272,20 +285,28 @@ __device__ __forceinline__ void decode_range(const DecodeParams &P, const int s,
         }
         __syncthreads();
         if (w != 0) return;
-        float M = sm_m[0];
+        float M;
+        auto merge = [&](const int nb) {
+            M = sm_m[0];
 #pragma unroll
-        for (int i = 1; i < W; ++i) M = fmaxf(M, sm_m[i]);
-        l = 0.f;
+            for (int i = 1; i < nb; ++i) M = fmaxf(M, sm_m[i]);
+            l = 0.f;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
-        // (not fully unrolled: sixteen waves' worth of LDS reads hoisted at once would spill)
+            for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+            // (not fully unrolled: sixteen waves' worth of LDS reads hoisted at once would spill)
 #pragma unroll 2
-        for (int i = 0; i < W; ++i) {
-            const float f = __builtin_amdgcn_exp2f(sm_m[i] - M);
-            l = __builtin_fmaf(sm_l[i], f, l);
+            for (int i = 0; i < nb; ++i) {
+                const float f = __builtin_amdgcn_exp2f(sm_m[i] - M);
+                l = __builtin_fmaf(sm_l[i], f, l);
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[e] = __builtin_fmaf(sm_acc[i][c * EPL + e], f, acc[e]);
-        }
+                for (int e = 0; e < EPL; ++e) acc[e] = __builtin_fmaf(sm_acc[i][c * EPL + e], f, acc[e]);
+            }
+        };
+        // (the usual case with its loop bounds known at compile time)
+        if (active == W)
+            merge(W);
+        else
+            merge(active);
         m = M;
     }
 }

@@ -358,6 +358,16 @@ def test_edge_context_lengths(pa):
         print(dtype, run_and_compare(pa, w, partitions=(0, PS, 256)))
 
 
+@pytest.mark.parametrize("dtype,D,B", [("f16", 128, 16), ("bf16", 128, 32), ("f32", 64, 16)])
+def test_one_long_sequence_among_short_ones(pa, dtype, D, B):
+    # the launch is planned from the 2048-token sequence; the short items leave most of their workgroup's
+    # waves without a chunk (those exit before the merge, which then covers the busy waves only)
+    rng = np.random.default_rng(77)
+    lens = np.concatenate([[2048], rng.integers(1, 65, size=40), [0, 1, 16, 17, 255, 256, 257]])
+    w = W.independent_sequences("skewed", dtype, 3, D, B, lens, seed=78)
+    print(dtype, run_and_compare(pa, w, partitions=(0, 512)))
+
+
 def test_empty_context_gives_zero_row(pa):
     w = W.independent_sequences("zeros", "f16", 2, 128, 16, np.array([0, 40, 0, 300]), seed=6)
     v = W.make_values(w)
