@@ -523,17 +523,8 @@ __global__ __launch_bounds__(W *kWave) __attribute__((amdgpu_waves_per_eu(4, 8))
     split_merge_store<DT, W>(Q, sm_region, sm_m, sm_l, members, P.out, (int64_t)qs, 1, H, h);
 }
 
-// More than 16 queries per sequence: grid = (sequence, block of 64 queries, head).  The four
-// waves of the workgroup own 16 query columns each and share every K/V tile: the workgroup
-// loads steps of two tiles into LDS together (each thread one 16-byte fragment per tile and
-// array), double-buffered, one barrier per step, with the next step's loads in flight while
-// the current one is computed.  So K/V comes from memory once per 64 queries.  With several
-// blocks of queries per sequence the same K/V is wanted again soon by a neighbouring workgroup
-// (same head, so the same XCD): the loads then leave it in the caches (STREAM unset: 750 ->
-// 650 us at 256 queries per sequence; with one block per sequence streaming loads are 3% faster).
-// (Measured and not adopted: 128 queries per workgroup, two sets of 16 columns per wave sharing
-// every LDS fragment - 199 registers, two waves per SIMD: 695 us at 256 queries, 376 instead
-// of 280 us at 64.)
+// More than 16 queries per sequence: grid = (sequence, block of queries, head); the kernel itself
+// follows the load helpers below.
 // One 16-byte-per-lane load straight from global memory into LDS (no register staging): lane i
 // fetches from src_uniform + its own lane_offset and the data lands at lds_base + 16 i.  Completion counts
 // on vmcnt like any vector load; the compiler does not know that the instruction writes LDS, so
@@ -563,10 +554,28 @@ __device__ __forceinline__ void wait_vector_loads_but()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// NQ sets of 16 query columns per wave: 64 NQ queries per workgroup.  Every K and V^T fragment a wave
-// reads from LDS serves its NQ sets, which is what the LDS bandwidth asks for: a 16x16x32 product
-// takes 16 cycles of a SIMD and its K or V^T operand is 1 KiB of LDS reads, against 128 bytes per
-// cycle for the four SIMDs together (measured: ~100 for ds_read_b128, ~50 for the transposing read).
+// More than 16 queries per sequence.  Grid = (sequence, block of 64 NQ queries, head); the four waves
+// of a workgroup own NQ sets of 16 query columns each and share every K/V tile, so K/V comes from
+// memory once per 64 NQ queries (NQ = 1 up to 64 queries per sequence, 2 beyond).
+//   Loads   every thread moves one 16-byte fragment of each K and V tile of a 32-token step straight
+//           into a ring of NS LDS stages (load16_to_lds); NS - 1 steps are in flight while one is
+//           computed, one barrier per step.  With several blocks of queries per sequence the same
+//           K/V is wanted again soon by the neighbouring workgroup (same head: with 40 heads the
+//           same XCD), so the loads then leave it in the caches (STREAM unset).
+//   Compute pair_step: 24 NQ matrix instructions per step and wave; each K and V^T fragment read
+//           from LDS serves the wave's NQ sets.
+// What bounds it (measured on MI355X): not the matrix pipes - a SIMD issues one vector or matrix
+// instruction at a time, ~4.5 cycles per vector instruction and 8 per 16x16x32 product whatever the
+// number of resident waves, so the softmax and conversion arithmetic between the products costs
+// more issue time than the products; the kernel is written to that count (pair_step).  Next come
+// the LDS reads (a product's 1 KiB K or V^T operand against ~100 B/clk for ds_read_b128 and ~50
+// for the transposing read, per compute unit) - hence the NQ sets per fragment - and, at one block
+// of queries per sequence, the output rows: 256-byte pieces scattered at the stride of a token
+// cost ~1.7 us per MB on top of the read stream whichever store flavour or workgroup placement
+// (non-temporal or plain, XCD-contiguous items or round-robin) is used.
+// Measured and not adopted: a deeper ring or more resident workgroups (no change: the loads are
+// not latency-bound), wave priorities that would put one wave's products beside another's
+// arithmetic (no change), work items laid out contiguously per XCD (worse on mixed lengths).
 template <int DT, int B, bool STREAM, int NQ>
 __global__ __launch_bounds__(4 * kWave) __attribute__((amdgpu_waves_per_eu(NQ == 1 ? 4 : 2, 8))) void pa_multi_block_kernel(
     const DecodeParams P)
@@ -597,6 +606,7 @@ __global__ __launch_bounds__(4 * kWave) __attribute__((amdgpu_waves_per_eu(NQ ==
     if (q0 >= qlen || n <= 0) return;
     const int wg_members = qlen - q0 < QB ? qlen - q0 : QB;
     const int wg_hi = n - qlen + q0 + wg_members;      // tokens the last query of the workgroup sees
+    if (wg_hi <= 0) return;                            // (more queries than tokens: outside the interface)
     const int nsteps = (wg_hi + STEP * kTileTokens - 1) / (STEP * kTileTokens);
     // this wave's NQ sets of 16 columns: set j holds queries q0 + QW w + 16 j + (0 .. 15)
     QueryCols Q[NQ];
