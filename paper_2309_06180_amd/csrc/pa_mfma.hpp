@@ -192,9 +192,10 @@ __device__ __forceinline__ void tile_step(QueryCols &Q, const char *kt, const ch
 //     8g+0..3) and of the second (slots 8g+4..7), so the V^T operand is two transposing reads
 //     side by side, and the leading and trailing 16-bit pieces of P go through two instructions
 //     on the same V^T registers (no register copies);
-//   - f16: the factor 2^14 that keeps small weights in the range of the 16-bit pieces is part of
+//   - f16: the factor 2^6 that keeps small weights in the range of the 16-bit pieces is part of
 //     the exponent, so it is in the running sum as well and cancels in the final division.
-constexpr float kPairShiftF16 = 14.0f;
+constexpr float kPairSlack = 8.0f;        // log2 units: a weight is at most 2^8
+constexpr float kPairShiftF16 = 6.0f;     // so the f16 pieces hold at most 2^14
 // An opaque 1.0f in a scalar register: p * one - (float)h is then a fused multiply-add with one 16-bit
 // operand, which the compiler issues as a single v_fma_mix_f32 (it would turn p - (float)h into a
 // conversion and a subtraction).  Vector instructions are what this kernel is bound by: measured,
@@ -275,8 +276,14 @@ __device__ __forceinline__ void pair_step(QueryCols (&Q)[NQ], const uint32_t pai
         }
         const float tmax = fmaxf(fmaxf(fmaxf(x[j][0], x[j][1]), fmaxf(x[j][2], x[j][3])),
                                  fmaxf(fmaxf(x[j][4], x[j][5]), fmaxf(x[j][6], x[j][7])));
-        m_new[j] = fmaxf(Q[j].m, quad_rows_max(tmax));
-        moved = moved || m_new[j] > Q[j].m;
+        // The reference point of the exponents follows the running maximum lazily: it moves only
+        // when a score exceeds it by more than kPairSlack, so weights reach 2^kPairSlack at most and
+        // the 33 multiplications that rescale a query's sums are rare instead of the rule (with
+        // 32 queries in a wave some maximum moves in almost every step).  Any reference point gives
+        // the same softmax; sums and products share it.
+        const float qmax = quad_rows_max(tmax);
+        m_new[j] = qmax > Q[j].m + kPairSlack ? qmax : Q[j].m;
+        moved = moved || m_new[j] != Q[j].m;
     }
     if (__any(moved)) {
 #pragma unroll
