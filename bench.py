@@ -62,7 +62,7 @@ def parse():
                          "layer cache write + decode")
     ap.add_argument("--multi-query", action="store_true",
                     help="instead of the step benchmark: pa_decode_multi at the OPT-13B shape for several q_len")
-    ap.add_argument("--q-lens", default="1,4,16,64,256",
+    ap.add_argument("--q-lens", default="1,4,16,64,128,256",
                     help="--multi-query: the q_len values to run, comma separated")
     ap.add_argument("--paging-overhead", action="store_true",
                     help="instead of the step benchmark: pa_decode over randomly placed blocks against the same "
@@ -340,7 +340,7 @@ def calibration_copy(pa, torch, dev, H=40, B=16, D=128, dtype=None):
     return {"kernel": "copy_blocks_kernel", "bytes_read": nbytes, "bytes_written": nbytes}
 
 
-def multi_query(pa, W, np, torch, dev, q_lens=(1, 4, 16, 64, 256), calibrate=False):
+def multi_query(pa, W, np, torch, dev, q_lens=(1, 4, 16, 64, 128, 256), calibrate=False):
     """pa_decode_multi at the OPT-13B layer shape: every sequence brings its last min(ctx, q_len) tokens as
     queries.  Per row a roofline: algorithmic bytes = K and V of every cached token once + q in + out;
     algorithmic flops = 4*D per (query, visible token) pair (both products, causal).  The bound is the one
