@@ -237,8 +237,8 @@ pa_status pa_decode_shared_planned(void *out, const void *q, const void *k_cache
  * (causal), by the same formula as pa_decode; q_len_s = 1 is pa_decode.
  * Runs on the matrix cores.  With max_q_len <= 16 one workgroup per (sequence,
  * head) serves all of a sequence's queries and K/V is read once; beyond that
- * one workgroup serves 64 queries and K/V is read once per 64 queries (from
- * the caches, mostly, after the first time).
+ * one workgroup serves 64 queries (max_q_len <= 64) or 128, and K/V is read
+ * once per workgroup (from the caches, mostly, after the first time).
  *
  *   out, q        [q_start[S]][H][D] dtype, rows of sequence s at q_start[s] ..
  *   q_start       device [S+1] int32, non-decreasing, q_start[0] = 0
