@@ -276,27 +276,39 @@ def test_multi_query_every_width(pa):
 
 
 def test_multi_query_sharp_softmax(pa):
-    # queries scaled by 8: one token dominates, the weights' two 16-bit pieces must carry it
+    # queries scaled by 8: one token dominates, the weights' two 16-bit pieces must carry it; at more than 64
+    # queries per sequence the exponents' reference point moves lazily (only past 2^8), which scores that keep
+    # rising along the context (K rows scaled by their position) exercise step after step
     for dtype in ("f16", "bf16"):
         lens = np.array([300, 77, 1200, 16], dtype=np.int64)
-        q_lens = np.array([64, 16, 40, 16], dtype=np.int64)
-        w = W.independent_sequences("multi_sharp", dtype, 2, 128, 16, lens, seed=91)
-        v = W.make_values(w)
-        dw = DeviceWorkload(w, v)
-        gpu_cache_ops(pa, dw)
-        kc, vc = oracle_cache_ops(w, v)
-        q_start = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
-        rng = np.random.default_rng(92)
-        q = W.to_storage(8.0 * rng.standard_normal((int(q_start[-1]), 2, 128)).astype(np.float32), dtype)
-        for qmax, qs in ((64, q_start),):
+        for q_lens, rising in (([64, 16, 40, 16], False), ([200, 77, 130, 16], False), ([256, 16, 100, 5], True)):
+            q_lens = np.array(q_lens, dtype=np.int64)
+            w = W.independent_sequences("multi_sharp", dtype, 2, 128, 16, lens, seed=91)
+            v = W.make_values(w)
+            dw = DeviceWorkload(w, v)
+            gpu_cache_ops(pa, dw)
+            kc, vc = oracle_cache_ops(w, v)
+            kdev = dw.k_cache
+            if rising:
+                # token at position t of every sequence gets its K row scaled by (1 + t / 64)
+                kf = W.storage_to_f64(kc, dtype)
+                for sq, n in enumerate(lens):
+                    for t in range(int(n)):
+                        b, o = w.block_tables[sq, t // 16], t % 16
+                        kf[b, :, o, :] *= 1.0 + t / 64.0
+                kc = W.to_storage(kf.astype(np.float32), dtype)
+                kdev = to_dev(kc, dtype)
+            q_start = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
+            rng = np.random.default_rng(92)
+            q = W.to_storage(8.0 * rng.standard_normal((int(q_start[-1]), 2, 128)).astype(np.float32), dtype)
             dq = to_dev(q, dtype)
             out = torch.full_like(dq, float("nan"))
-            pa.pa_decode_multi(out, dq, dw.k_cache, dw.v_cache, dw.block_tables, dw.context_lens, to_dev(qs),
-                               qmax, 16, float(w.scale), w.max_context_len)
+            pa.pa_decode_multi(out, dq, kdev, dw.v_cache, dw.block_tables, dw.context_lens, to_dev(q_start),
+                               int(q_lens.max()), 16, float(w.scale), w.max_context_len)
             torch.cuda.synchronize()
-            ref = oracle.decode_multi(q, kc, vc, w.block_tables, w.context_lens, qs, w.scale, dtype)
+            ref = oracle.decode_multi(q, kc, vc, w.block_tables, w.context_lens, q_start, w.scale, dtype)
             err = float(np.abs(out_to_f64(out, dtype) - ref).max())
-            assert err <= TOL[dtype], "sharp multi %s: %g" % (dtype, err)
+            assert err <= TOL[dtype], "sharp multi %s q_len %s rising=%s: %g" % (dtype, q_lens, rising, err)
 
 
 def test_multi_query_one_hot_operands_fail_by_position(pa):
