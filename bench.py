@@ -432,6 +432,13 @@ def cache_ops(pa, np, torch, dev):
         us_in = _time_us(lambda: pa.pa_swap_blocks([hk], [hv], [kc], [vc], in_pairs), 10, torch)
         res["swap_blocks"].append({"blocks": N, "out_us": us_out, "out_GBps": moved / us_out / 1e3,
                                    "in_us": us_in, "in_GBps": moved / us_in / 1e3})
+    # for scale: the runtime's own device-to-device copy of one contiguous buffer of the size of 4096 block
+    # pairs (K and V), same accounting (bytes read plus bytes written)
+    n_elems = 2 * 4096 * H * B * D
+    a = torch.empty(n_elems, dtype=torch.float16, device=dev)
+    b = torch.empty_like(a)
+    us = _time_us(lambda: b.copy_(a), 50, torch)
+    res["reference_contiguous_device_copy"] = {"bytes_each_way": n_elems * 2, "us": us, "GBps": 2 * n_elems * 2 / us / 1e3}
     res["metric"] = "cache_ops_read_plus_write_GBps"
     res["shape"] = "H=40, D=128, B=16, fp16, pool of 8192 blocks"
     print(json.dumps(res))
