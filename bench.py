@@ -112,12 +112,19 @@ def profiled_traffic(workload_name):
         return None, "no counter summary"
 
 
-def _time_calls_us(fn, iters, torch, warmup=3):
+def _time_calls_us(fn, iters, torch, warmup=3, warm_ms=0.0):
     """Per-call GPU time of `fn` in us: an event pair around every call, on torch's current stream, which
-    is the stream the library launches on.  Returns the list of the `iters` durations."""
+    is the stream the library launches on.  Returns the list of the `iters` durations.  `warm_ms`: keep
+    launching untimed for at least that long first (after seconds of host-only work the device's clocks
+    take tens of milliseconds of load to come back up)."""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < warm_ms:
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
     ends = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
     for i in range(iters):
@@ -134,8 +141,8 @@ def _stats(us):
 
 
 def _time_us(fn, iters, torch):
-    """Median per-call time in us."""
-    return _stats(_time_calls_us(fn, iters, torch))["median_us"]
+    """Median per-call time in us (after 20 ms of untimed launches: see _time_calls_us)."""
+    return _stats(_time_calls_us(fn, iters, torch, warm_ms=20.0))["median_us"]
 
 
 def block_size_sweep(pa, W, np, torch, dev):
@@ -498,7 +505,7 @@ def others(pa, W, np, torch, dev, iters=30):
             else:
                 pa.pa_shared_plan(bt, cl, H, D, B, NB, tdt[w.dtype], mcl, ws)
                 fn = lambda: pa.pa_decode_shared_planned(o, q, kc, vc, bt, cl, B, float(w.scale), mcl, ws)
-            st = _stats(_time_calls_us(fn, iters, torch))
+            st = _stats(_time_calls_us(fn, iters, torch, warm_ms=50.0))
             torch.cuda.synchronize()
             got = storage_to_f64(_to_host_storage(o, w.dtype, np, torch), w.dtype)[rows[:, 0], rows[:, 1]]
             st["frac_of_hbm_peak"] = algo / st["median_us"] / 1e3 / HBM_PEAK_GBPS
