@@ -255,9 +255,9 @@ int auto_partition(int S, int H, int max_context_len)
     return ps >= max_context_len ? 0 : (int)ps;
 }
 
-// Several queries per sequence.  Up to 16 of them: one workgroup of eight waves per (sequence,
-// head) that split the tiles.  More: one workgroup of four waves per (sequence, 64 queries,
-// head) that share every tile through LDS.
+// Several queries per sequence.  Up to 16 of them: one workgroup per (sequence, head) whose waves
+// split the tiles.  More: one workgroup of four waves per (sequence, block of queries, head) that
+// share every tile through LDS, 64 queries per block up to 64 per sequence, 128 beyond.
 template <int DT, int B>
 void launch_multi_b(const DecodeArgs &a, int max_q_len)
 {
