@@ -267,8 +267,8 @@ __device__ __forceinline__ void pair_step(QueryCols (&Q)[NQ], const uint32_t pai
                 S1[j][v] = (t0 + 16 + 4 * g + v <= Q[j].limit) ? S1[j][v] : -INFINITY;
             }
         }
-        // (scaled first: products of a multiplication are known to be canonical numbers, so the maxima
-        // below are one instruction each)
+        // (scaled after the masking, by a positive scale: products of a multiplication are known to be
+        // canonical numbers, so the maxima below are one instruction each)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             x[j][v] = S0[j][v] * scale_log2;
@@ -674,7 +674,24 @@ __global__ __launch_bounds__(4 * kWave) __attribute__((amdgpu_waves_per_eu(NQ ==
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc) asm volatile("" ::"v"(__builtin_bit_cast(u32x4_t, Q[j].qf[cc])));
     }
-    const float scale_log2 = P.scale_log2;
+    // pair_step masks scores with -inf before it scales them, which wants a positive scale: a negative
+    // one moves into the queries (a sign flip, exact), and zero becomes 1e-30 (every product then rounds
+    // to the same exponent, the uniform weights that zero asks for, and -inf stays -inf)
+    float scale_log2 = P.scale_log2;
+    if (scale_log2 < 0.f) {
+        scale_log2 = -scale_log2;
+#pragma unroll
+        for (int j = 0; j < NQ; ++j) {
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+                Q[j].qf[cc].x ^= 0x80008000u;
+                Q[j].qf[cc].y ^= 0x80008000u;
+                Q[j].qf[cc].z ^= 0x80008000u;
+                Q[j].qf[cc].w ^= 0x80008000u;
+            }
+        }
+    }
+    scale_log2 = scale_log2 < 1e-30f ? 1e-30f : scale_log2;
     for (int st0 = 0; st0 < nsteps; st0 += NS) {
 #pragma unroll
         for (int j = 0; j < NS; ++j) {

@@ -225,9 +225,10 @@ def test_shared_plan_reused_across_layers(pa):
 # ---------------------------------------------------------------------------
 # several query tokens per sequence (causal), on the matrix cores
 # ---------------------------------------------------------------------------
-def multi_case(pa, dtype, lens, q_lens, H=3, B=16, seed=41):
+def multi_case(pa, dtype, lens, q_lens, H=3, B=16, seed=41, scale=None):
     lens, q_lens = np.asarray(lens, dtype=np.int64), np.asarray(q_lens, dtype=np.int64)
     w = W.independent_sequences("multi", dtype, H, 128, B, lens, seed=seed)
+    scale = w.scale if scale is None else np.float32(scale)
     v = W.make_values(w)
     dw = DeviceWorkload(w, v)
     gpu_cache_ops(pa, dw)
@@ -239,14 +240,24 @@ def multi_case(pa, dtype, lens, q_lens, H=3, B=16, seed=41):
     dq = to_dev(q, dtype)
     out = torch.full_like(dq, float("nan"))
     pa.pa_decode_multi(out, dq, dw.k_cache, dw.v_cache, dw.block_tables, dw.context_lens, to_dev(q_start),
-                       int(q_lens.max()), B, float(w.scale), w.max_context_len)
+                       int(q_lens.max()), B, float(scale), w.max_context_len)
     torch.cuda.synchronize()
-    ref = oracle.decode_multi(q, kc, vc, w.block_tables, w.context_lens, q_start, w.scale, dtype)
+    ref = oracle.decode_multi(q, kc, vc, w.block_tables, w.context_lens, q_start, scale, dtype)
     got = out_to_f64(out, dtype)
     assert np.isfinite(got).all()
     err = float(np.abs(got - ref).max())
     assert err <= TOL[dtype], "multi %s: max abs err %g" % (dtype, err)
     return err
+
+
+def test_multi_query_other_scales(pa):
+    # the scale is an argument (Sec. 4.1 fixes 1/sqrt(d); the interface does not): negative (the smallest
+    # products win), zero (uniform weights) and large, through all three several-query kernels
+    lens = [300, 77, 1200, 16, 130]
+    for q_lens in ([16, 16, 9, 16, 1], [64, 33, 40, 16, 17], [200, 77, 256, 16, 130]):
+        for dtype in ("f16", "bf16"):
+            for scale in (-0.0883883, 0.0, 0.7):
+                print(dtype, max(q_lens), scale, multi_case(pa, dtype, lens, q_lens, H=2, seed=61, scale=scale))
 
 
 def test_multi_query_decode(pa):
@@ -378,6 +389,19 @@ def test_one_long_sequence_among_short_ones(pa, dtype, D, B):
     lens = np.concatenate([[2048], rng.integers(1, 65, size=40), [0, 1, 16, 17, 255, 256, 257]])
     w = W.independent_sequences("skewed", dtype, 3, D, B, lens, seed=78)
     print(dtype, run_and_compare(pa, w, partitions=(0, 512)))
+
+
+@pytest.mark.parametrize("scale", [-0.0883883, 0.0, 0.7])
+def test_other_scales(pa, scale):
+    # the scale is an argument of the interface: negative (the smallest products win), zero (uniform weights)
+    # and large, through the one-pass, split-context and sharing-aware calls
+    for dtype in ("f16", "bf16"):
+        w = mixed_sharing_workload(dtype)
+        w.scale = np.float32(scale)
+        print(dtype, scale, run_and_compare(pa, w, partitions=(0, 64, SHARED)))
+    w = W.independent_sequences("scales_f32", "f32", 2, 64, 16, np.array([1, 40, 300, 17]), seed=15)
+    w.scale = np.float32(scale)
+    print("f32", scale, run_and_compare(pa, w, partitions=(0, 64)))
 
 
 def test_empty_context_gives_zero_row(pa):
