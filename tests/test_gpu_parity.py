@@ -322,6 +322,44 @@ def test_multi_query_sharp_softmax(pa):
             assert err <= TOL[dtype], "sharp multi %s q_len %s rising=%s: %g" % (dtype, q_lens, rising, err)
 
 
+def test_multi_query_graph_replay(pa):
+    # the several-query kernels hold no state between launches: a captured call replays with new queries
+    # written in place and matches the eager result bit for bit, for each of the three kernels
+    lens = np.array([300, 77, 1200, 16, 130], dtype=np.int64)
+    w = W.independent_sequences("multi_graph", "f16", 2, 128, 16, lens, seed=71)
+    v = W.make_values(w)
+    dw = DeviceWorkload(w, v)
+    gpu_cache_ops(pa, dw)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(6)
+    for q_lens in ([16, 16, 9, 16, 1], [64, 33, 40, 16, 17], [200, 77, 256, 16, 130]):
+        q_start = to_dev(np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32))
+        T = int(sum(q_lens))
+        q = torch.randn((T, 2, 128), device="cuda", generator=gen).to(torch.float16)
+        out = torch.empty_like(q)
+
+        def call():
+            pa.pa_decode_multi(out, q, dw.k_cache, dw.v_cache, dw.block_tables, dw.context_lens, q_start,
+                               max(q_lens), 16, float(w.scale), w.max_context_len)
+
+        call()
+        torch.cuda.synchronize()
+        first = out.clone()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            call()
+        for it in range(3):
+            q.copy_(torch.randn(q.shape, device="cuda", generator=gen).to(q.dtype))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            replayed = out.clone()
+            call()                                        # eager work between replays
+            torch.cuda.synchronize()
+            assert torch.equal(replayed, out), "q_len %d: replay %d differs from eager" % (max(q_lens), it)
+            assert not torch.equal(replayed, first)
+
+
 def test_multi_query_one_hot_operands_fail_by_position(pa):
     # K, V and Q made of single ones: every logit is 0 or 1 and every output element is a
     # small rational that names the (query, token, dimension) it came from, so a slip in an
