@@ -322,6 +322,40 @@ def test_multi_query_sharp_softmax(pa):
             assert err <= TOL[dtype], "sharp multi %s q_len %s rising=%s: %g" % (dtype, q_lens, rising, err)
 
 
+def test_multi_query_deterministic_and_placement_invariant(pa):
+    # same bits run to run, and when the physical blocks are relabelled by a permutation with their data
+    # moved along (Sec. 4.1: placement is free; the summation order follows logical positions only)
+    lens = np.array([300, 77, 1200, 16, 130], dtype=np.int64)
+    w = W.independent_sequences("multi_place", "bf16", 2, 128, 16, lens, seed=73)
+    v = W.make_values(w)
+    dw = DeviceWorkload(w, v)
+    gpu_cache_ops(pa, dw)
+    perm = np.random.default_rng(4).permutation(w.num_blocks)
+    inv = np.argsort(perm)
+    kc2 = dw.k_cache[to_dev(inv)].contiguous()           # new block perm[i] holds old block i
+    vc2 = dw.v_cache[to_dev(inv)].contiguous()
+    bt = w.block_tables.copy()
+    for s in range(w.num_seqs):
+        nb = (int(w.context_lens[s]) + 15) // 16
+        bt[s, :nb] = perm[bt[s, :nb]]
+    bt2 = to_dev(bt)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(8)
+    for q_lens in ([16, 16, 9, 16, 1], [64, 33, 40, 16, 17], [200, 77, 256, 16, 130]):
+        q_start = to_dev(np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32))
+        q = torch.randn((int(sum(q_lens)), 2, 128), device="cuda", generator=gen).to(torch.bfloat16)
+        outs = []
+        for kc, vc, tables in ((dw.k_cache, dw.v_cache, dw.block_tables), (dw.k_cache, dw.v_cache, dw.block_tables),
+                               (kc2, vc2, bt2)):
+            out = torch.full_like(q, float("nan"))
+            pa.pa_decode_multi(out, q, kc, vc, tables, dw.context_lens, q_start, max(q_lens), 16, float(w.scale),
+                               w.max_context_len)
+            torch.cuda.synchronize()
+            outs.append(out)
+        assert torch.equal(outs[0], outs[1]), "q_len %d: run-to-run difference" % max(q_lens)
+        assert torch.equal(outs[0], outs[2]), "q_len %d: result depends on block placement" % max(q_lens)
+
+
 def test_multi_query_graph_replay(pa):
     # the several-query kernels hold no state between launches: a captured call replays with new queries
     # written in place and matches the eager result bit for bit, for each of the three kernels
