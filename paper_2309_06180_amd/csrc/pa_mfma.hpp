@@ -566,7 +566,9 @@ __device__ __forceinline__ void wait_vector_loads_but()
 // memory once per 64 NQ queries (NQ = 1 up to 64 queries per sequence, 2 beyond).
 //   Loads   every thread moves one 16-byte fragment of each K and V tile of a 32-token step straight
 //           into a ring of NS LDS stages (load16_to_lds); NS - 1 steps are in flight while one is
-//           computed, one barrier per step.  With several blocks of queries per sequence the same
+//           computed, one barrier per step.  NS = 2 with four workgroups per compute unit (NQ = 1) or
+//           3 with three (NQ = 2, 156 registers): the depth of the ring matters little, the number
+//           of resident workgroups does (NQ = 2: four stages with two workgroups measure 6% slower).  With several blocks of queries per sequence the same
 //           K/V is wanted again soon by the neighbouring workgroup (same head: with 40 heads the
 //           same XCD), so the loads then leave it in the caches (STREAM unset).
 //   Compute pair_step: 24 NQ matrix instructions per step and wave; each K and V^T fragment read
@@ -580,16 +582,16 @@ __device__ __forceinline__ void wait_vector_loads_but()
 // of queries per sequence, the output rows: 256-byte pieces scattered at the stride of a token
 // cost ~1.7 us per MB on top of the read stream whichever store flavour or workgroup placement
 // (non-temporal or plain, XCD-contiguous items or round-robin) is used.
-// Measured and not adopted: a deeper ring or more resident workgroups (no change: the loads are
-// not latency-bound), wave priorities that would put one wave's products beside another's
-// arithmetic (no change), work items laid out contiguously per XCD (worse on mixed lengths).
+// Measured and not adopted: a deeper ring (no change: the loads are not latency-bound), wave
+// priorities that would put one wave's products beside another's arithmetic (no change), work
+// items laid out contiguously per XCD (worse on mixed lengths).
 template <int DT, int B, bool STREAM, int NQ>
-__global__ __launch_bounds__(4 * kWave) __attribute__((amdgpu_waves_per_eu(NQ == 1 ? 4 : 2, 8))) void pa_multi_block_kernel(
+__global__ __launch_bounds__(4 * kWave) __attribute__((amdgpu_waves_per_eu(NQ == 1 ? 4 : 3, 8))) void pa_multi_block_kernel(
     const DecodeParams P)
 {
     using Tr = Traits<DT>;
     typedef char __attribute__((address_space(3))) *lds_char_ptr;
-    constexpr int W = 4, ROW_BYTES = 256, STEP = 2, NS = NQ == 1 ? 2 : 4, QW = 16 * NQ, QB = W * QW;
+    constexpr int W = 4, ROW_BYTES = 256, STEP = 2, NS = NQ == 1 ? 2 : 3, QW = 16 * NQ, QB = W * QW;
     constexpr int TILE_LDS = 2 * kTileTokens * ROW_BYTES;            // K tile, then V tile, rows unpadded
     constexpr int STAGE_LDS = STEP * TILE_LDS;
     constexpr int LOADS_PER_STEP = 2 * STEP;                         // per thread
